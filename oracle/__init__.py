@@ -1,0 +1,119 @@
+"""fp64 CPU oracle for the multi-head-attention decode step (TEST INFRASTRUCTURE).
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this package.  It shares no code with the HIP path and never imports it.
+
+The arithmetic lives in ``mha_oracle.c`` (plain C, double precision); this
+module compiles it with gcc on first use and marshals numpy arrays to it.
+
+``mha_reference``  multi-head attention by its definition (Eq. 1, Eq. 2/6).
+``el_reference``   the same quantity in the evaluation order of Eq. 9; used by
+                   the tests to check the losslessness identity on the oracle.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mha_oracle.c")
+_LIB = os.path.join(_HERE, "libmha_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile mha_oracle.c into libmha_oracle.so next to it (gcc, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC",
+               "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            dp = ctypes.POINTER(ctypes.c_double)
+            ip = ctypes.POINTER(ctypes.c_int32)
+            sig = [ctypes.c_int] * 6 + [dp, ip, dp] + [dp] * 8 + [dp]
+            for name in ("mha_oracle", "el_oracle"):
+                fn = getattr(lib, name)
+                fn.argtypes = sig
+                fn.restype = ctypes.c_int
+            lib.oracle_num_threads.restype = ctypes.c_int
+            _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loop over batch elements will use."""
+    return int(_load().oracle_num_threads())
+
+
+def _f64(a, shape, name):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+    if a.shape != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _call(fn_name, H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, heads, d_k):
+    H = np.asarray(H)
+    queries = np.asarray(queries)
+    if H.ndim != 3 or queries.ndim != 3:
+        raise ValueError("H must be [B, n, d_m] and queries [B, beam, d_m]")
+    B, n, d_m = H.shape
+    beam = queries.shape[1]
+    hd = heads * d_k
+    H = _f64(H, (B, n, d_m), "H")
+    queries = _f64(queries, (B, beam, d_m), "queries")
+    Wq = _f64(Wq, (d_m, hd), "Wq")
+    Wk = _f64(Wk, (d_m, hd), "Wk")
+    Wv = _f64(Wv, (d_m, hd), "Wv")
+    Wo = _f64(Wo, (hd, d_m), "Wo")
+    bq = _f64(bq, (hd,), "bq")
+    bk = _f64(bk, (hd,), "bk")
+    bv = _f64(bv, (hd,), "bv")
+    bo = _f64(bo, (d_m,), "bo")
+    lp = None
+    if lengths is not None:
+        lengths = np.ascontiguousarray(np.asarray(lengths, dtype=np.int32))
+        if lengths.shape != (B,):
+            raise ValueError("lengths must be [B]")
+        lp = lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    out = np.empty((B, beam, d_m), dtype=np.float64)
+    rc = getattr(_load(), fn_name)(B, beam, n, heads, d_m, d_k, _ptr(H), lp, _ptr(queries),
+                                   _ptr(Wq), _ptr(bq), _ptr(Wk), _ptr(bk), _ptr(Wv), _ptr(bv),
+                                   _ptr(Wo), _ptr(bo), _ptr(out))
+    if rc != 0:
+        raise ValueError(f"{fn_name} rejected its arguments (code {rc}); lengths must lie in [1, n]")
+    return out
+
+
+def mha_reference(H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, *, heads, d_k):
+    """Eq. 6: sum_i softmax(Q_i K_i^T / sqrt(d_k)) V_i W_i^O (+ b^O), in float64.
+
+    H [B,n,d_m]; lengths [B] or None; queries [B,beam,d_m]; Wq/Wk/Wv [d_m,h*d_k];
+    Wo [h*d_k,d_m]; biases may be None.  Returns out [B,beam,d_m] float64.
+    """
+    return _call("mha_oracle", H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, heads, d_k)
+
+
+def el_reference(H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, *, heads, d_k):
+    """Eq. 9: the expanded-query evaluation order, in float64 (oracle self-check only)."""
+    return _call("el_oracle", H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, heads, d_k)
