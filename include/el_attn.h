@@ -1,0 +1,173 @@
+/*
+ * el_attn.h -- C ABI of the EL-attention incremental decode step for MI355X (gfx950).
+ *
+ * What the library computes.  For every batch element b (one matrix of hidden
+ * states H_b with a valid prefix of lengths[b] positions) and every beam j (one
+ * query vector), the multi-head attention output of appendix B, Eq. 6,
+ *
+ *     out[b,j] = sum_i softmax( Q_i K_i^T / sqrt(d_k) ) V_i W_i^O  (+ b^O),
+ *     Q_i = q W_i^Q + b_i^Q,  K_i = H_b W_i^K + b_i^K,  V_i = H_b W_i^V + b_i^V,
+ *
+ * evaluated in the EL-attention order of Eq. 5 / Eq. 9: the query is expanded per
+ * head to model width, EL-Q_i = Q_i (W_i^K)^T, scored directly against the
+ * unprojected H_b, the probabilities are applied to H_b, and the result goes
+ * through W_i^V and W_i^O (the seven steps of the EL "encoder_decoder_attention"
+ * routine of appendix A, Algorithm 3).  No per-head key or value is ever built.
+ * The key bias only adds a per-row constant to the scores and cancels in the
+ * softmax; the value bias contributes sum_i b_i^V W_i^O because probabilities sum
+ * to one (remark closing appendix B); the library uses both facts.
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never frees caller memory and keeps no reference to H, lengths, queries or
+ *     out after a call returns.  Weights are copied at prepare time.
+ *   - Row-major everywhere.  Head i owns columns [i*d_k, (i+1)*d_k) of W^Q, W^K,
+ *     W^V and rows [i*d_k, (i+1)*d_k) of W^O (the concatenation form noted under
+ *     Eq. 2).  Weights are used as x . W (Eq. 2: W_i^{Q,K,V} in R^{d_m x d_k}).
+ *   - Calls are asynchronous on the HIP stream passed in (`stream` is a
+ *     hipStream_t cast to void*; NULL is the default stream).  Nothing
+ *     synchronises.  el_attn_decode_step never allocates.
+ *   - Errors are return codes.  Argument errors are found before any HIP call is
+ *     made, so they can be exercised on a host without a GPU.
+ *   - One GPU, one context per attention layer.  A context may be used from one
+ *     stream at a time (its workspace is shared by its calls).
+ */
+#ifndef EL_ATTN_H
+#define EL_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct el_attn_ctx el_attn_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    EL_OK = 0,
+    EL_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, size beyond the prepared maxima */
+    EL_ERR_UNSUPPORTED = 2, /* a shape or dtype no kernel covers (e.g. heads*d_k != d_model)     */
+    EL_ERR_ALLOC = 3,       /* device or host allocation failed in prepare                       */
+    EL_ERR_HIP = 4,         /* a HIP runtime call failed (no device, launch error)               */
+    EL_ERR_WORKSPACE = 5    /* decode_step without a bound workspace, or one too small           */
+} el_status;
+
+typedef enum { EL_F32 = 0, EL_F16 = 1, EL_BF16 = 2 } el_dtype;
+
+/* flags */
+#define EL_FLAG_FORCE_GENERIC 1u /* run the plain fp32-arithmetic kernels even where an MFMA path exists */
+
+typedef struct {
+    int32_t heads;     /* h                                                         */
+    int32_t d_model;   /* d_m                                                       */
+    int32_t d_k;       /* per-head width; heads*d_k must equal d_model              */
+    int32_t dtype;     /* el_dtype: storage type of H, queries, weights and biases  */
+    int32_t out_dtype; /* el_dtype of `out`: EL_F32 or the same as `dtype`          */
+    int32_t max_batch; /* largest B a decode_step call will pass                    */
+    int32_t max_beam;  /* largest beam                                              */
+    int32_t max_n;     /* largest padded key length n                               */
+    uint32_t flags;    /* EL_FLAG_*                                                 */
+} el_attn_config;
+
+/*
+ * Step a0 (once per attention layer, off the per-step path): take the layer's
+ * projection weights, keep private packed copies, and fold the biases as the
+ * closing remark of appendix B allows: c_out = b^O + sum_i b_i^V W_i^O (Eq. 8/9)
+ * is computed here, and b^K is accepted but never read (it cancels, Eq. 7).
+ *
+ *   Wq, Wk, Wv  [d_model, heads*d_k]   device, `dtype`
+ *   Wo          [heads*d_k, d_model]   device, `dtype`
+ *   bq, bk, bv  [heads*d_k] or NULL    device, `dtype`
+ *   bo          [d_model]   or NULL    device, `dtype`
+ *
+ * The copies are enqueued on `stream`; the caller may release its weights once
+ * the stream has passed this point.  On success *out_ctx owns device memory
+ * until el_attn_destroy.  Errors: INVALID_ARG (null cfg/weights/out_ctx, sizes
+ * < 1), UNSUPPORTED (heads*d_k != d_model, unknown dtype, out_dtype neither
+ * EL_F32 nor dtype), ALLOC, HIP.
+ */
+el_status el_attn_prepare(const el_attn_config *cfg,
+                          const void *Wq, const void *bq,
+                          const void *Wk, const void *bk,
+                          const void *Wv, const void *bv,
+                          const void *Wo, const void *bo,
+                          void *stream, el_attn_ctx **out_ctx);
+
+/*
+ * Scratch memory one decode step needs at the prepared maxima (expanded
+ * queries, split partials, projected rows).  The caller allocates at least
+ * this many bytes of device memory, 256-byte aligned, and binds it; the
+ * library neither frees it nor touches it outside decode_step /
+ * expand_query.  Its contents need not be initialised.
+ */
+size_t el_attn_workspace_bytes(const el_attn_ctx *ctx);
+el_status el_attn_bind_workspace(el_attn_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/*
+ * One incremental decode step (steps a1..a7 of Algorithm 3's attention routine):
+ *
+ *   a1  Qp    = queries . W^Q + b^Q                              (per beam row)
+ *   a2  EL-Q  = Qp_i . (W_i^K)^T / sqrt(d_k)   -> [B, heads*beam, d_model]   (Eq. 5)
+ *   a3  S     = EL-Q . H_b^T   over t < lengths[b]                           (Eq. 9)
+ *   a4  P     = softmax_t(S)   (fp32)                                        (Eq. 1)
+ *   a5  X     = P . H_b                                  -> [B, heads*beam, d_model]
+ *   a6  A     = X_i . W_i^V                              -> [B*beam, heads*d_k] (Eq. 5/8)
+ *   a7  out   = A . W^O + c_out                          -> [B, beam, d_model]  (Eq. 2)
+ *
+ *   H        [B, n, d_model], row stride d_model, batch stride H_batch_stride
+ *            ELEMENTS (>= n*d_model); device, `dtype`.  Rows t >= lengths[b] are
+ *            never read; they may hold anything, NaN included.
+ *   lengths  [B] int32 device, each in [1, n]; NULL means every row has length n.
+ *            Values are not validated on the device; a value outside [1, n] is
+ *            undefined behaviour of the caller.
+ *   queries  [B, beam, d_model] contiguous, device, `dtype`.
+ *   out      [B, beam, d_model] contiguous, device, `out_dtype`.
+ *
+ * Self-attention over a per-beam history is the same call with B := B*beam and
+ * beam := 1 (section 3.1.1: the state is the previous layer's output, appended
+ * by the caller before the call).
+ *
+ * Errors: INVALID_ARG (null ctx/H/queries/out; B, beam or n < 1 or beyond the
+ * prepared maxima; H_batch_stride < n*d_model), WORKSPACE, HIP (launch failure).
+ */
+el_status el_attn_decode_step(el_attn_ctx *ctx,
+                              const void *H, int64_t H_batch_stride,
+                              const int32_t *lengths,
+                              const void *queries,
+                              void *out,
+                              int32_t B, int32_t beam, int32_t n,
+                              void *stream);
+
+/*
+ * Diagnostic export of steps a1+a2 alone (Eq. 5, EL-Q_i = (Q W_i^Q + b_i^Q)(W_i^K)^T,
+ * already divided by sqrt(d_k)):  elq_out [B, heads*beam, d_model] float32, device,
+ * row r = i*beam + j holds head i of beam j.  Uses the bound workspace.
+ */
+el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq_out,
+                               int32_t B, int32_t beam, void *stream);
+
+/*
+ * Tuning knob, never semantics: number of contiguous key-range splits the
+ * attention core uses per batch element (each split is one workgroup; partial
+ * results are merged with the log-sum-exp rule).  0 restores the automatic
+ * choice.  Must not exceed el_attn_max_splits().
+ */
+el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits);
+int32_t el_attn_max_splits(void);
+
+/* 1 if decode_step on this context runs the MFMA kernels, 0 if the generic fp32 ones. */
+int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);
+
+/* Release the context and its packed weights (not the workspace, which the caller owns). */
+el_status el_attn_destroy(el_attn_ctx *ctx);
+
+const char *el_attn_status_string(el_status s);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t el_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EL_ATTN_H */

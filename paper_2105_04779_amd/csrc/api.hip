@@ -1,0 +1,244 @@
+// Host side of the C ABI declared in include/el_attn.h: argument validation, context and
+// workspace bookkeeping, and the per-step launch sequence.  No kernel lives here.
+#include <new>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "el_internal.h"
+
+using namespace el;
+
+namespace {
+
+constexpr int32_t kVersion = 100; // 0.1.0
+
+bool valid_dtype(int dt) { return dt == EL_F32 || dt == EL_F16 || dt == EL_BF16; }
+
+int round_up16(int v) { return (v + 15) / 16 * 16; }
+
+struct WsLayout {
+    size_t off_Qp, off_ELQ, off_Xp, off_ML, off_Xn, off_A, total;
+};
+
+WsLayout ws_layout(const el_attn_ctx *c, int B, int beam)
+{
+    // Offsets are computed for the prepared maxima so that a bound workspace is valid for
+    // every smaller call; B and beam are only used by callers that want exact sizes.
+    (void)B; (void)beam;
+    const size_t mb = (size_t)c->cfg.max_batch, mx = (size_t)c->cfg.max_beam;
+    const size_t d_m = (size_t)c->cfg.d_model, hd = (size_t)c->hd, Rp = (size_t)c->Rpad_max;
+    WsLayout L;
+    size_t o = 0;
+    L.off_Qp = o;  o = align_up(o + mb * mx * hd * sizeof(float), 256);
+    L.off_ELQ = o; o = align_up(o + mb * Rp * d_m * sizeof(float), 256);
+    L.off_Xp = o;  o = align_up(o + mb * kMaxParts * Rp * d_m * sizeof(float), 256);
+    L.off_ML = o;  o = align_up(o + mb * kMaxParts * Rp * 2 * sizeof(float), 256);
+    L.off_Xn = o;  o = align_up(o + mb * Rp * d_m * sizeof(float), 256);
+    L.off_A = o;   o = align_up(o + mb * mx * hd * sizeof(float), 256);
+    L.total = o;
+    return L;
+}
+
+Workspace carve(const el_attn_ctx *c)
+{
+    const WsLayout L = ws_layout(c, 0, 0);
+    char *base = (char *)c->ws_base;
+    Workspace w;
+    w.Qp = (float *)(base + L.off_Qp);
+    w.ELQ = (void *)(base + L.off_ELQ);
+    w.Xp = (float *)(base + L.off_Xp);
+    w.ML = (float *)(base + L.off_ML);
+    w.Xn = (float *)(base + L.off_Xn);
+    w.A = (float *)(base + L.off_A);
+    return w;
+}
+
+void free_weights(el_attn_ctx *c)
+{
+    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, (void *)c->w.c_out};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    std::memset(&c->w, 0, sizeof(c->w));
+}
+
+// Number of key-range parts for the generic core: enough workgroups to occupy the chip
+// when B*R is small, never more parts than 64-position slices of the shortest useful range.
+int auto_parts_generic(const Problem &p)
+{
+    const long rows = (long)p.B * p.R;
+    int parts = 1;
+    if (rows < 1024) parts = (int)((1024 + rows - 1) / rows);
+    const int by_len = p.n / 64 > 0 ? p.n / 64 : 1;
+    if (parts > by_len) parts = by_len;
+    if (parts > kMaxParts) parts = kMaxParts;
+    return parts < 1 ? 1 : parts;
+}
+
+el_status check_step_args(const el_attn_ctx *ctx, const void *queries, int32_t B, int32_t beam)
+{
+    if (!ctx || !queries) return EL_ERR_INVALID_ARG;
+    if (B < 1 || beam < 1) return EL_ERR_INVALID_ARG;
+    if (B > ctx->cfg.max_batch || beam > ctx->cfg.max_beam) return EL_ERR_INVALID_ARG;
+    return EL_OK;
+}
+
+Problem make_problem(const el_attn_ctx *ctx, const void *H, int64_t stride, const int32_t *lengths,
+                     const void *queries, void *out, int B, int beam, int n)
+{
+    Problem p;
+    p.B = B; p.beam = beam; p.n = n;
+    p.heads = ctx->cfg.heads; p.d_m = ctx->cfg.d_model; p.d_k = ctx->cfg.d_k; p.hd = ctx->hd;
+    p.R = ctx->cfg.heads * beam;
+    p.dtype = ctx->cfg.dtype; p.out_dtype = ctx->cfg.out_dtype;
+    p.H = H; p.H_batch_stride = stride; p.lengths = lengths; p.queries = queries; p.out = out;
+    return p;
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t el_attn_version(void) { return kVersion; }
+
+int32_t el_attn_max_splits(void) { return kMaxParts; }
+
+const char *el_attn_status_string(el_status s)
+{
+    switch (s) {
+    case EL_OK: return "ok";
+    case EL_ERR_INVALID_ARG: return "invalid argument";
+    case EL_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case EL_ERR_ALLOC: return "allocation failed";
+    case EL_ERR_HIP: return "HIP runtime error";
+    case EL_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+el_status el_attn_prepare(const el_attn_config *cfg,
+                          const void *Wq, const void *bq, const void *Wk, const void *bk,
+                          const void *Wv, const void *bv, const void *Wo, const void *bo,
+                          void *stream, el_attn_ctx **out_ctx)
+{
+    (void)bk; // cancels in the softmax (Eq. 7): accepted, never read
+    if (out_ctx) *out_ctx = nullptr;
+    if (!cfg || !out_ctx || !Wq || !Wk || !Wv || !Wo) return EL_ERR_INVALID_ARG;
+    if (cfg->heads < 1 || cfg->d_model < 1 || cfg->d_k < 1) return EL_ERR_INVALID_ARG;
+    if (cfg->max_batch < 1 || cfg->max_beam < 1 || cfg->max_n < 1) return EL_ERR_INVALID_ARG;
+    if (!valid_dtype(cfg->dtype) || !valid_dtype(cfg->out_dtype)) return EL_ERR_UNSUPPORTED;
+    if (cfg->out_dtype != EL_F32 && cfg->out_dtype != cfg->dtype) return EL_ERR_UNSUPPORTED;
+    if ((int64_t)cfg->heads * cfg->d_k != cfg->d_model) return EL_ERR_UNSUPPORTED;
+    if (cfg->d_model > kGenericMaxDm) return EL_ERR_UNSUPPORTED;
+    if ((int64_t)cfg->heads * cfg->max_beam > 65535 || cfg->max_batch > 65535) return EL_ERR_UNSUPPORTED;
+
+    el_attn_ctx *c = new (std::nothrow) el_attn_ctx;
+    if (!c) return EL_ERR_ALLOC;
+    std::memset(c, 0, sizeof(*c));
+    c->cfg = *cfg;
+    c->hd = cfg->heads * cfg->d_k;
+    c->Rpad_max = round_up16(cfg->heads * cfg->max_beam);
+    c->ws_need = ws_layout(c, 0, 0).total;
+    c->use_mfma_core = 0;
+
+    hipStream_t s = (hipStream_t)stream;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return EL_ERR_HIP; }
+
+    const size_t es = dtype_size(cfg->dtype);
+    const size_t wbytes = (size_t)cfg->d_model * c->hd * es;
+    struct { void **dst; const void *src; size_t bytes; } copies[] = {
+        {&c->w.Wq, Wq, wbytes}, {&c->w.Wk, Wk, wbytes}, {&c->w.Wv, Wv, wbytes}, {&c->w.Wo, Wo, wbytes},
+        {&c->w.bq, bq, (size_t)c->hd * es},
+    };
+    for (auto &cp : copies) {
+        if (!cp.src) continue;
+        if (hipMalloc(cp.dst, cp.bytes) != hipSuccess) { free_weights(c); delete c; return EL_ERR_ALLOC; }
+        if (hipMemcpyAsync(*cp.dst, cp.src, cp.bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) {
+            free_weights(c); delete c; return EL_ERR_HIP;
+        }
+    }
+    if (hipMalloc((void **)&c->w.c_out, (size_t)cfg->d_model * sizeof(float)) != hipSuccess) {
+        free_weights(c); delete c; return EL_ERR_ALLOC;
+    }
+    if (launch_cout(c, bv, bo, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+
+    *out_ctx = c;
+    return EL_OK;
+}
+
+size_t el_attn_workspace_bytes(const el_attn_ctx *ctx) { return ctx ? ctx->ws_need : 0; }
+
+el_status el_attn_bind_workspace(el_attn_ctx *ctx, void *dev_ptr, size_t bytes)
+{
+    if (!ctx || !dev_ptr) return EL_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_ptr & 255u) != 0) return EL_ERR_INVALID_ARG;
+    if (bytes < ctx->ws_need) return EL_ERR_WORKSPACE;
+    ctx->ws_base = dev_ptr;
+    ctx->ws_bytes = bytes;
+    return EL_OK;
+}
+
+el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits)
+{
+    if (!ctx || splits < 0 || splits > kMaxParts) return EL_ERR_INVALID_ARG;
+    ctx->splits_override = splits;
+    return EL_OK;
+}
+
+int32_t el_attn_uses_mfma(const el_attn_ctx *ctx)
+{
+    return (ctx && ctx->use_mfma_core && !(ctx->cfg.flags & EL_FLAG_FORCE_GENERIC)) ? 1 : 0;
+}
+
+el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq_out,
+                               int32_t B, int32_t beam, void *stream)
+{
+    el_status st = check_step_args(ctx, queries, B, beam);
+    if (st != EL_OK) return st;
+    if (!elq_out) return EL_ERR_INVALID_ARG;
+    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, nullptr, 0, nullptr, queries, nullptr, B, beam, 1);
+    if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    if (launch_elq_generic(ctx, p, ws.Qp, elq_out, s) != hipSuccess) return EL_ERR_HIP;
+    return EL_OK;
+}
+
+el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_stride,
+                              const int32_t *lengths, const void *queries, void *out,
+                              int32_t B, int32_t beam, int32_t n, void *stream)
+{
+    el_status st = check_step_args(ctx, queries, B, beam);
+    if (st != EL_OK) return st;
+    if (!H || !out) return EL_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
+    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
+    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
+
+    // a1, a2
+    if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
+    // a3-a5
+    int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
+    if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
+    if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
+    // a6, a7
+    if (launch_vproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    if (launch_oproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    return EL_OK;
+}
+
+el_status el_attn_destroy(el_attn_ctx *ctx)
+{
+    if (!ctx) return EL_ERR_INVALID_ARG;
+    free_weights(ctx);
+    delete ctx;
+    return EL_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,223 @@
+"""Thin Python binding of the C ABI in include/el_attn.h (argument marshalling only).
+
+Every step of the decode path runs in the HIP library; torch is used for device
+memory and the stream handle, nothing else.  Loading fails loudly when the
+library has not been built -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libelattn.so")
+
+EL_OK, EL_ERR_INVALID_ARG, EL_ERR_UNSUPPORTED, EL_ERR_ALLOC, EL_ERR_HIP, EL_ERR_WORKSPACE = range(6)
+EL_F32, EL_F16, EL_BF16 = 0, 1, 2
+EL_FLAG_FORCE_GENERIC = 1
+
+DTYPE_CODES = {"f32": EL_F32, "f16": EL_F16, "bf16": EL_BF16}
+
+EXPORTED_SYMBOLS = (
+    "el_attn_prepare", "el_attn_workspace_bytes", "el_attn_bind_workspace", "el_attn_decode_step",
+    "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_uses_mfma",
+    "el_attn_destroy", "el_attn_status_string", "el_attn_version",
+)
+
+
+class ElAttnConfig(ctypes.Structure):
+    _fields_ = [
+        ("heads", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_k", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("max_batch", ctypes.c_int32), ("max_beam", ctypes.c_int32), ("max_n", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+class ElAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2105_04779_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.el_attn_prepare.argtypes = [ctypes.POINTER(ElAttnConfig)] + [vp] * 8 + [vp, ctypes.POINTER(vp)]
+    lib.el_attn_prepare.restype = ctypes.c_int
+    lib.el_attn_workspace_bytes.argtypes = [vp]
+    lib.el_attn_workspace_bytes.restype = sz
+    lib.el_attn_bind_workspace.argtypes = [vp, vp, sz]
+    lib.el_attn_bind_workspace.restype = ctypes.c_int
+    lib.el_attn_decode_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, vp]
+    lib.el_attn_decode_step.restype = ctypes.c_int
+    lib.el_attn_expand_query.argtypes = [vp, vp, vp, i32, i32, vp]
+    lib.el_attn_expand_query.restype = ctypes.c_int
+    lib.el_attn_set_splits.argtypes = [vp, i32]
+    lib.el_attn_set_splits.restype = ctypes.c_int
+    lib.el_attn_max_splits.argtypes = []
+    lib.el_attn_max_splits.restype = i32
+    lib.el_attn_uses_mfma.argtypes = [vp]
+    lib.el_attn_uses_mfma.restype = i32
+    lib.el_attn_destroy.argtypes = [vp]
+    lib.el_attn_destroy.restype = ctypes.c_int
+    lib.el_attn_status_string.argtypes = [ctypes.c_int]
+    lib.el_attn_status_string.restype = ctypes.c_char_p
+    lib.el_attn_version.argtypes = []
+    lib.el_attn_version.restype = i32
+    return lib
+
+
+lib = _load()
+
+
+# ---- functions with the C names (raw pointers as ints / None) ---------------------------------
+def status_string(status: int) -> str:
+    return lib.el_attn_status_string(int(status)).decode()
+
+
+el_attn_status_string = status_string
+
+
+def el_attn_version() -> int:
+    return int(lib.el_attn_version())
+
+
+def el_attn_max_splits() -> int:
+    return int(lib.el_attn_max_splits())
+
+
+def el_attn_prepare(cfg: ElAttnConfig, Wq, bq, Wk, bk, Wv, bv, Wo, bo, stream=None):
+    """Returns (status, ctx_handle).  Pointers are device addresses (int) or None."""
+    ctx = ctypes.c_void_p()
+    st = lib.el_attn_prepare(ctypes.byref(cfg), Wq, bq, Wk, bk, Wv, bv, Wo, bo, stream, ctypes.byref(ctx))
+    return st, ctx
+
+
+def el_attn_workspace_bytes(ctx) -> int:
+    return int(lib.el_attn_workspace_bytes(ctx))
+
+
+def el_attn_bind_workspace(ctx, dev_ptr, nbytes) -> int:
+    return lib.el_attn_bind_workspace(ctx, dev_ptr, nbytes)
+
+
+def el_attn_decode_step(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream=None) -> int:
+    return lib.el_attn_decode_step(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream)
+
+
+def el_attn_expand_query(ctx, queries, elq_out, B, beam, stream=None) -> int:
+    return lib.el_attn_expand_query(ctx, queries, elq_out, B, beam, stream)
+
+
+def el_attn_set_splits(ctx, splits) -> int:
+    return lib.el_attn_set_splits(ctx, splits)
+
+
+def el_attn_uses_mfma(ctx) -> int:
+    return int(lib.el_attn_uses_mfma(ctx))
+
+
+def el_attn_destroy(ctx) -> int:
+    return lib.el_attn_destroy(ctx)
+
+
+# ---- torch convenience wrapper (still marshalling only) ------------------------------------
+def _torch_dtype(code):
+    import torch
+    return {EL_F32: torch.float32, EL_F16: torch.float16, EL_BF16: torch.bfloat16}[code]
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class ElAttention:
+    """One attention layer prepared for decode steps on the current CUDA/HIP device.
+
+    weights: dict with Wq, Wk, Wv [d_m, h*d_k], Wo [h*d_k, d_m] and optional bq, bk, bv, bo
+    as torch tensors on the device in the storage dtype.
+    """
+
+    def __init__(self, weights, *, heads, d_k, dtype, max_batch, max_beam, max_n,
+                 out_dtype="f32", flags=0):
+        import torch
+        self._torch = torch
+        d_m = weights["Wq"].shape[0]
+        self.cfg = ElAttnConfig(heads, d_m, d_k, DTYPE_CODES[dtype], DTYPE_CODES[out_dtype],
+                                max_batch, max_beam, max_n, flags)
+        td = _torch_dtype(self.cfg.dtype)
+        for k, v in weights.items():
+            if v is not None:
+                if not v.is_cuda or v.dtype != td or not v.is_contiguous():
+                    raise ValueError(f"weight {k} must be a contiguous device tensor of dtype {td}")
+        g = lambda k: _ptr(weights.get(k))
+        st, ctx = el_attn_prepare(self.cfg, g("Wq"), g("bq"), g("Wk"), g("bk"), g("Wv"), g("bv"),
+                                  g("Wo"), g("bo"), _stream_handle())
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_prepare")
+        self.ctx = ctx
+        self.d_m = d_m
+        nbytes = el_attn_workspace_bytes(ctx)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=weights["Wq"].device)
+        st = el_attn_bind_workspace(ctx, _ptr(self.workspace), nbytes)
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_bind_workspace")
+
+    @property
+    def uses_mfma(self) -> bool:
+        return bool(el_attn_uses_mfma(self.ctx))
+
+    def set_splits(self, splits: int):
+        st = el_attn_set_splits(self.ctx, splits)
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_set_splits")
+
+    def decode_step(self, H, lengths, queries, out=None):
+        """H [B,n,d_m] (batch stride free, rows contiguous), lengths int32 [B] or None,
+        queries [B,beam,d_m] contiguous.  Returns out [B,beam,d_m]."""
+        torch = self._torch
+        B, n, d_m = H.shape
+        beam = queries.shape[1]
+        if H.stride(2) != 1 or H.stride(1) != d_m:
+            raise ValueError("rows of H must be contiguous with stride d_m")
+        if not queries.is_contiguous():
+            raise ValueError("queries must be contiguous")
+        if out is None:
+            out = torch.empty((B, beam, d_m), dtype=_torch_dtype(self.cfg.out_dtype), device=H.device)
+        if lengths is not None and lengths.dtype != torch.int32:
+            raise ValueError("lengths must be int32")
+        st = el_attn_decode_step(self.ctx, _ptr(H), H.stride(0) if B > 1 else n * d_m, _ptr(lengths),
+                                 _ptr(queries), _ptr(out), B, beam, n, _stream_handle())
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_decode_step")
+        return out
+
+    def expand_query(self, queries):
+        torch = self._torch
+        B, beam, d_m = queries.shape
+        elq = torch.empty((B, self.cfg.heads * beam, d_m), dtype=torch.float32, device=queries.device)
+        st = el_attn_expand_query(self.ctx, _ptr(queries), _ptr(elq), B, beam, _stream_handle())
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_expand_query")
+        return elq
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            el_attn_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,81 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ea():
+    from paper_2105_04779_amd import el_attn
+    return el_attn
+
+
+def test_library_exports_every_declared_symbol(ea):
+    header = open(os.path.join(ROOT, "include", "el_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(el_attn_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found in the header"
+    assert declared == set(ea.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(ea.lib, name), f"{name} is declared but not exported"
+
+
+def test_version_and_strings(ea):
+    assert ea.el_attn_version() >= 100
+    assert ea.el_attn_max_splits() >= 1
+    assert ea.status_string(ea.EL_OK) == "ok"
+    for s in range(1, 6):
+        assert ea.status_string(s) not in ("ok", "unknown status")
+    assert ea.status_string(99) == "unknown status"
+
+
+def _cfg(ea, **kw):
+    base = dict(heads=4, d_model=64, d_k=16, dtype=ea.EL_F32, out_dtype=ea.EL_F32,
+                max_batch=2, max_beam=2, max_n=32, flags=0)
+    base.update(kw)
+    return ea.ElAttnConfig(*[base[k] for k in ("heads", "d_model", "d_k", "dtype", "out_dtype",
+                                               "max_batch", "max_beam", "max_n", "flags")])
+
+
+FAKE = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+
+
+def test_prepare_rejects_bad_arguments_before_any_device_work(ea):
+    I, U = ea.EL_ERR_INVALID_ARG, ea.EL_ERR_UNSUPPORTED
+    ok = _cfg(ea)
+    st, _ = ea.el_attn_prepare(ok, None, None, FAKE, None, FAKE, None, FAKE, None)
+    assert st == I
+    st, _ = ea.el_attn_prepare(ok, FAKE, None, FAKE, None, FAKE, None, None, None)
+    assert st == I
+    for bad in (dict(heads=0), dict(d_model=0), dict(d_k=-1), dict(max_batch=0), dict(max_beam=0), dict(max_n=0)):
+        st, _ = ea.el_attn_prepare(_cfg(ea, **bad), FAKE, None, FAKE, None, FAKE, None, FAKE, None)
+        assert st == I, bad
+    for bad in (dict(d_k=8), dict(dtype=7), dict(out_dtype=9), dict(dtype=ea.EL_F16, out_dtype=ea.EL_BF16),
+                dict(d_model=16384, heads=256, d_k=64)):
+        st, _ = ea.el_attn_prepare(_cfg(ea, **bad), FAKE, None, FAKE, None, FAKE, None, FAKE, None)
+        assert st == U, bad
+
+
+def test_null_context_is_rejected_everywhere(ea):
+    I = ea.EL_ERR_INVALID_ARG
+    assert ea.el_attn_workspace_bytes(None) == 0
+    assert ea.el_attn_bind_workspace(None, FAKE, 1024) == I
+    assert ea.el_attn_decode_step(None, FAKE, 64, None, FAKE, FAKE, 1, 1, 1) == I
+    assert ea.el_attn_expand_query(None, FAKE, FAKE, 1, 1) == I
+    assert ea.el_attn_set_splits(None, 1) == I
+    assert ea.el_attn_uses_mfma(None) == 0
+    assert ea.el_attn_destroy(None) == I
+
+
+def test_prepare_without_a_device_reports_hip_error(ea):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    st, ctx = ea.el_attn_prepare(_cfg(ea), FAKE, None, FAKE, None, FAKE, None, FAKE, None)
+    assert st == ea.EL_ERR_HIP
+    assert not ctx.value
