@@ -15,7 +15,7 @@ constexpr int32_t kVersion = 100; // 0.1.0
 
 bool valid_dtype(int dt) { return dt == EL_F32 || dt == EL_F16 || dt == EL_BF16; }
 
-int round_up16(int v) { return (v + 15) / 16 * 16; }
+int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 struct WsLayout {
     size_t off_Qp, off_ELQ, off_Xp, off_ML, off_Xn, off_A, total;
@@ -137,9 +137,9 @@ el_status el_attn_prepare(const el_attn_config *cfg,
     std::memset(c, 0, sizeof(*c));
     c->cfg = *cfg;
     c->hd = cfg->heads * cfg->d_k;
-    c->Rpad_max = round_up16(cfg->heads * cfg->max_beam);
+    c->Rpad_max = round_up64(cfg->heads * cfg->max_beam);
     c->ws_need = ws_layout(c, 0, 0).total;
-    c->use_mfma_core = 0;
+    c->use_mfma_core = core_mfma_supported(cfg->dtype, cfg->d_model) ? 1 : 0;
 
     hipStream_t s = (hipStream_t)stream;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return EL_ERR_HIP; }
@@ -220,13 +220,20 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
 
-    // a1, a2
+    // a1
     if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
-    if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
-    // a3-a5
-    int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
-    if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
-    if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
+    if (el_attn_uses_mfma(ctx)) {
+        // a2 in fp16 for the MFMA core, a3-a5 on MFMA, merge of the key-range partials
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override);
+        if (launch_elq_f16(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        if (launch_core_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        if (launch_merge_exp2(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+    } else {
+        if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
+        const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
+        if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
+        if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
+    }
     // a6, a7
     if (launch_vproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
     if (launch_oproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;

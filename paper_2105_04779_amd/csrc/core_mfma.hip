@@ -1,0 +1,438 @@
+// MFMA attention core for gfx950: steps a3-a5 of the EL-attention decode step (Algorithm 3's two
+// products over the hidden states and the softmax between them; Eq. 9 with K = V = H).
+//
+// One workgroup (4 wavefronts, one per SIMD) owns a contiguous range of 32-row tiles of one
+// batch element's H and up to 64 expanded-query rows.  Every H tile is pulled from HBM once,
+// straight into LDS (global_load_lds, no registers in between), converted there to fp16 when the
+// storage type is bf16, and then used twice from LDS:
+//
+//   S^T = H_tile . ELQ^T      v_mfma_f32_16x16x32_f16, A = H rows (ds_read_b128), B = ELQ (registers)
+//   X^T += H_tile^T . P^T     same instruction, A = H columns (ds_read_b64_tr_b16 transposing
+//                             reads), B = P (the score accumulators, exponentiated in place)
+//
+// Working on the transposes puts the query row in lane%16 for both products, so the softmax
+// statistics, the probabilities and the output accumulators of a row all live in the same lanes
+// and P never moves between lanes.  Scores arrive pre-multiplied by log2(e)/sqrt(d_k), so the
+// softmax is exp2 of a difference; max and sum are kept per row in fp32, the running reference
+// maximum is only advanced (and the accumulators rescaled) when it would grow by more than 2^10.
+//
+// Each wavefront keeps its 16 rows of ELQ (fp16) and its 16 x d_m fp32 accumulators in registers
+// for the whole range.  With fewer than 64 rows the spare wavefronts take alternate tiles and
+// produce partial results of their own; all partials (key-range splits and wavefront parities)
+// are combined afterwards by the log-sum-exp merge.
+#include "el_internal.h"
+
+namespace el {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef short s4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+#define EL_LDS(T) __attribute__((address_space(3))) T
+#define EL_GLOBAL(T) __attribute__((address_space(1))) T
+
+constexpr int kTileRows = 32;
+constexpr float kRescaleStep = 10.0f; // log2 units: probabilities stay below 2^10
+
+struct CoreArgs {
+    const void *H;
+    int64_t h_stride;        // elements between batch elements
+    const int32_t *lengths;
+    const f16_t *elq;        // [B, Rs, DM] fp16, scaled by log2(e)/sqrt(d_k), pad rows zero
+    float *Xp;               // [B, parts, Rs, DM]
+    float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
+    int n, B, R, Rs, S, nblocks;
+};
+
+// 16-byte chunk swizzle inside a tile row: a bijection of the low four chunk bits that makes both
+// the row-wise b128 reads and the transposing b64 reads spread over all LDS banks.
+__device__ __forceinline__ int row_swizzle(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
+
+__device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x)
+{
+    const float lo = __uint_as_float(x << 16);
+    const float hi = __uint_as_float(x & 0xffff0000u);
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+
+template <int DM, bool BF16, int NRG>
+__global__ void __launch_bounds__(256)
+k_core_mfma(const CoreArgs a)
+{
+    constexpr int ROWB = DM * 2;                  // bytes per tile row in LDS (fp16)
+    constexpr int CPR = DM / 8;                   // 16-byte chunks per row
+    constexpr int TILE_BYTES = kTileRows * ROWB;
+    constexpr int DMA_PER_WAVE = TILE_BYTES / 1024 / 4;
+    constexpr int CHUNKS_PER_THREAD = kTileRows * CPR / 256;
+    constexpr int KCH = DM / 32;                  // k-chunks of the score product
+    constexpr int DB = DM / 16;                   // 16-column blocks of the output
+    constexpr int TS = 4 / NRG;                   // wavefronts sharing a row group (tile parities)
+    static_assert(CPR % 64 == 0, "a 1 KB LDS-DMA piece must not straddle tile rows");
+
+    __shared__ __attribute__((aligned(1024))) char F[TILE_BYTES]; // fp16 tile, swizzled, MFMA operand source
+    __shared__ __attribute__((aligned(1024))) char Rw[TILE_BYTES]; // raw landing zone of the next tile
+
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = l & 15, g = l >> 4;
+
+    // workgroup -> (batch element, key split, row block); workgroups that share an H range differ
+    // by multiples of 8 so they are dispatched to the same XCD (same L2).
+    const int id = blockIdx.x;
+    const int oct = id / (8 * a.nblocks), rem = id % (8 * a.nblocks);
+    const int rb = rem >> 3, group = oct * 8 + (rem & 7);
+    if (group >= a.B * a.S) return;
+    const int b = group / a.S, s = group % a.S;
+
+    const int rg = w % NRG, tsel = w / NRG;
+    const int row = rb * (16 * NRG) + 16 * rg + r16;   // expanded-query row of this lane
+
+    int len = a.lengths ? a.lengths[b] : a.n;
+    len = min(max(len, 1), a.n);
+    const int NT = (len + kTileRows - 1) / kTileRows;
+    const int k0 = (int)(((int64_t)NT * s) / a.S), k1 = (int)(((int64_t)NT * (s + 1)) / a.S);
+    const int nloc = k1 - k0;
+
+    const int parts = a.S * TS, part = s * TS + tsel;
+    float *ml_out = a.ML + (((size_t)b * parts + part) * a.Rs + row) * 2;
+    float *x_out = a.Xp + (((size_t)b * parts + part) * a.Rs + row) * DM;
+
+    const char *Hb = (const char *)a.H + (size_t)b * a.h_stride * 2;
+
+    // ---- ELQ rows of this wavefront: B operand of the score product ------------------------
+    h8 elq[KCH];
+    {
+        const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + 8 * g;
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) elq[c] = *(const h8 *)(src + 32 * c);
+    }
+
+    f4 X[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i) X[i] = f4{0.f, 0.f, 0.f, 0.f};
+    float m_ref = -INFINITY, l_sum = 0.f;
+
+    // ---- per-lane LDS addresses -------------------------------------------------------------
+    const EL_LDS(char) *Fl = (const EL_LDS(char) *)F;
+    int a_base[4]; // score product: row r16 (+16), chunk 4c+g
+    {
+        const int fx = row_swizzle(r16), cx = fx >> 2, gx = g ^ (fx & 3);
+#pragma unroll
+        for (int ci = 0; ci < 4; ++ci) a_base[ci] = r16 * ROWB + ((ci ^ cx) << 6) + (gx << 4);
+    }
+    int b_base[8]; // weighted sum: lane i=4k+q of block g reads row 4g+k (+16), columns 16db+4q..+3
+    {
+        const int k = r16 >> 2, q = r16 & 3, t_lo = 4 * g + k, ft = row_swizzle(t_lo);
+#pragma unroll
+        for (int di = 0; di < 8; ++di)
+            b_base[di] = t_lo * ROWB + ((((2 * di) + (q >> 1)) ^ ft) << 4) + (q & 1) * 8;
+    }
+
+    auto issue_dma = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < DMA_PER_WAVE; ++i) {
+            const int piece = w * DMA_PER_WAVE + i;          // 1 KB piece of the tile
+            const int trow = (piece * 64) / CPR;
+            const int cc = (piece * 64) % CPR + l;
+            const int t = kt * kTileRows + trow;
+            if (t < len)
+                __builtin_amdgcn_global_load_lds(
+                    (const EL_GLOBAL(void) *)(Hb + ((size_t)t * DM + (size_t)cc * 8) * 2),
+                    (EL_LDS(void) *)(Rw + piece * 1024), 16, 0, 0);
+        }
+    };
+
+    auto convert_chunk = [&](u4 v) {
+        if (BF16) {
+            v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
+            v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
+        }
+        return v;
+    };
+    // Raw tile -> fp16 tile in MFMA-friendly (swizzled) order.  Rows at or beyond len are written
+    // as zeros and their landing-zone bytes are never read.
+    auto convert_tile = [&](int kt) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));           // recompute the LDS addresses per tile instead of
+                                                // keeping 2 x CHUNKS_PER_THREAD of them in registers
+        if ((kt + 1) * kTileRows <= len) {        // full tile: no per-row checks, reads batched
+            constexpr int BATCH = 4;
+#pragma unroll
+            for (int i0 = 0; i0 < CHUNKS_PER_THREAD; i0 += BATCH) {
+                u4 v[BATCH];
+#pragma unroll
+                for (int e = 0; e < BATCH; ++e) v[e] = *(const u4 *)(Rw + ((i0 + e) * 256 + tid) * 16);
+#pragma unroll
+                for (int e = 0; e < BATCH; ++e) {
+                    const int idc = (i0 + e) * 256 + tid;
+                    const int trow = idc / CPR, cc = idc % CPR;
+                    *(u4 *)(F + trow * ROWB + ((cc ^ row_swizzle(trow)) << 4)) = convert_chunk(v[e]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
+                const int idc = i * 256 + tid;
+                const int trow = idc / CPR, cc = idc % CPR;
+                const int t = kt * kTileRows + trow;
+                u4 v = u4{0u, 0u, 0u, 0u};
+                if (t < len) v = convert_chunk(*(const u4 *)(Rw + idc * 16));
+                *(u4 *)(F + trow * ROWB + ((cc ^ row_swizzle(trow)) << 4)) = v;
+            }
+        }
+    };
+
+    if (nloc > 0) issue_dma(k0);
+
+    for (int kk = 0; kk < nloc; ++kk) {
+        const int kt = k0 + kk;
+        // Every wavefront drains its own LDS-DMA before the barrier: the conversion pass reads
+        // pieces that other wavefronts fetched, and the compiler only orders a wave's own accesses.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();            // tile kt has landed in Rw; all reads of F are done
+        convert_tile(kt);
+        __syncthreads();            // F holds tile kt; Rw is free
+        if (kk + 1 < nloc) issue_dma(kt + 1);
+        if (TS > 1 && (kk % TS) != tsel) continue;
+
+        // ---- scores: S^T[t, r] for the 32 rows of the tile --------------------------------
+        // Software-pipelined by hand in groups of four k-chunks: the LDS reads of group cc+1 are
+        // issued before the MFMAs of group cc; the scheduling barriers keep the compiler from
+        // hoisting every read to the top (which would spill the accumulators).
+        f4 s0a = {0.f, 0.f, 0.f, 0.f}, s0b = s0a, s1a = s0a, s1b = s0a;
+        {
+            h8 hb[2][4];
+            auto load_grp = [&](int cp, h8 *dst) {   // k-chunks 2cp, 2cp+1 for both 16-row halves
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int cidx = 2 * cp + e;
+                    dst[e] = *(const EL_LDS(h8) *)(Fl + a_base[cidx & 3] + (cidx >> 2) * 256);
+                    dst[2 + e] = *(const EL_LDS(h8) *)(Fl + a_base[cidx & 3] + (cidx >> 2) * 256 + 16 * ROWB);
+                }
+            };
+            load_grp(0, hb[0]);
+#pragma unroll
+            for (int cp = 0; cp < KCH / 2; ++cp) {
+                if (cp + 1 < KCH / 2) load_grp(cp + 1, hb[(cp + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                const h8 *hc = hb[cp & 1];
+                s0a = __builtin_amdgcn_mfma_f32_16x16x32_f16(hc[0], elq[2 * cp + 0], s0a, 0, 0, 0);
+                s1a = __builtin_amdgcn_mfma_f32_16x16x32_f16(hc[2], elq[2 * cp + 0], s1a, 0, 0, 0);
+                s0b = __builtin_amdgcn_mfma_f32_16x16x32_f16(hc[1], elq[2 * cp + 1], s0b, 0, 0, 0);
+                s1b = __builtin_amdgcn_mfma_f32_16x16x32_f16(hc[3], elq[2 * cp + 1], s1b, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        float sc[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { sc[j] = s0a[j] + s0b[j]; sc[4 + j] = s1a[j] + s1b[j]; }
+        if ((kt + 1) * kTileRows > len) {   // last, ragged tile: positions at or beyond len do not exist
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int t = kt * kTileRows + 16 * (j >> 2) + 4 * g + (j & 3);
+                if (t >= len) sc[j] = -INFINITY;
+            }
+        }
+
+        // ---- softmax bookkeeping (row = lane%16; its 32 scores sit in 4 lanes x 8 registers) ----
+        float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
+                         fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const bool grow = mx > m_ref + kRescaleStep;   // also true on the first tile (m_ref = -inf)
+        if (__any(grow)) {
+            const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - mx) : 1.0f;
+            if (grow) m_ref = mx;
+            l_sum *= alpha;
+#pragma unroll
+            for (int i = 0; i < DB; ++i) {
+                // one accumulator tuple at a time through arch VGPRs; the empty asm statements pin
+                // the register classes so the allocator does not move the whole array at once
+                f4 t = X[i];
+                asm volatile("" : "+v"(t));
+                t[0] *= alpha; t[1] *= alpha; t[2] *= alpha; t[3] *= alpha;
+                asm volatile("" : "+a"(t));
+                X[i] = t;
+            }
+        }
+        float pr[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { pr[j] = __builtin_amdgcn_exp2f(sc[j] - m_ref); psum += pr[j]; }
+        l_sum += psum;
+        h8 P;
+        {
+            const h2 p01 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[0], pr[1]));
+            const h2 p23 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[2], pr[3]));
+            const h2 p45 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[4], pr[5]));
+            const h2 p67 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[6], pr[7]));
+            P = h8{p01[0], p01[1], p23[0], p23[1], p45[0], p45[1], p67[0], p67[1]};
+        }
+
+        // ---- weighted sum: X^T[d, r] += sum_t H[t, d] P[r, t] ----------------------------------
+        // Same hand pipelining, in groups of eight 16-column blocks (16 transposing reads each).
+        {
+            typedef short s8 __attribute__((ext_vector_type(8)));
+            s4 tb[2][8];
+            auto load_grp = [&](int dq, s4 *dst) {    // 16-column blocks 4dq .. 4dq+3
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int db = 4 * dq + e;
+                    dst[2 * e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_base[db & 7] + (db >> 3) * 256));
+                    dst[2 * e + 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_base[db & 7] + (db >> 3) * 256 + 16 * ROWB));
+                }
+            };
+            load_grp(0, tb[0]);
+#pragma unroll
+            for (int dq = 0; dq < DB / 4; ++dq) {
+                if (dq + 1 < DB / 4) load_grp(dq + 1, tb[(dq + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                const s4 *tc = tb[dq & 1];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const s4 lo = tc[2 * e], hi = tc[2 * e + 1];
+                    const h8 A = __builtin_bit_cast(h8, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+                    X[4 * dq + e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, P, X[4 * dq + e], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- partial result of this wavefront -----------------------------------------------------
+    l_sum += __shfl_xor(l_sum, 16, 64);
+    l_sum += __shfl_xor(l_sum, 32, 64);
+    if (row < a.R) {
+        if (g == 0) { ml_out[0] = m_ref; ml_out[1] = l_sum; }
+        if (l_sum > 0.f) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) *(f4 *)(x_out + 16 * db + 4 * g) = X[db];
+        }
+    }
+}
+
+// a2 for the MFMA core: EL-Q in fp16, pre-multiplied by log2(e) (Qp already carries 1/sqrt(d_k)),
+// rows padded with zeros up to Rs.
+template <typename T>
+__global__ void k_elq_f16(const float *__restrict__ Qp, const T *__restrict__ Wk, f16_t *__restrict__ elq,
+                          int beam, int d_m, int d_k, int hd, int R, int Rs)
+{
+    const int d = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y, b = blockIdx.z;
+    if (d >= d_m) return;
+    float acc = 0.f;
+    if (r < R) {
+        const int i = r / beam, j = r % beam;
+        const float *qp = Qp + ((size_t)b * beam + j) * hd + (size_t)i * d_k;
+        const T *wk = Wk + (size_t)d * hd + (size_t)i * d_k;
+        for (int c = 0; c < d_k; ++c) acc = fmaf(qp[c], to_f32(wk[c]), acc);
+        acc *= 1.4426950408889634f;
+    }
+    elq[((size_t)b * Rs + r) * d_m + d] = (f16_t)acc;
+}
+
+// Log-sum-exp merge of partials whose reference maxima are in log2 units.
+__global__ void k_merge_exp2(const float *__restrict__ Xp, const float *__restrict__ ML, float *__restrict__ Xn,
+                             int d_m, int R, int Rs, int parts)
+{
+    const int d = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y, b = blockIdx.z;
+    if (d >= d_m) return;
+    float M = -INFINITY;
+    for (int p = 0; p < parts; ++p) {
+        const size_t rowi = ((size_t)b * parts + p) * Rs + r;
+        if (ML[rowi * 2 + 1] > 0.f) M = fmaxf(M, ML[rowi * 2]);
+    }
+    float num = 0.f, den = 0.f;
+    for (int p = 0; p < parts; ++p) {
+        const size_t rowi = ((size_t)b * parts + p) * Rs + r;
+        const float mp = ML[rowi * 2], lp = ML[rowi * 2 + 1];
+        if (lp > 0.f) {
+            const float wgt = exp2f(mp - M);
+            num = fmaf(wgt, Xp[rowi * d_m + d], num);
+            den = fmaf(wgt, lp, den);
+        }
+    }
+    Xn[((size_t)b * R + r) * d_m + d] = num / den;
+}
+
+// ---------------------------------------------------------------------------------------------
+bool core_mfma_supported(int dtype, int d_m)
+{
+    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024);
+}
+
+CorePlan plan_core_mfma(const Problem &p, int splits_override)
+{
+    CorePlan pl;
+    if (p.R <= 16) pl.nrg = 1;
+    else if (p.R <= 32) pl.nrg = 2;
+    else pl.nrg = 4;
+    pl.nblocks = (p.R + 16 * pl.nrg - 1) / (16 * pl.nrg);
+    pl.Rs = pl.nblocks * 16 * pl.nrg;
+    const int ts = 4 / pl.nrg;
+    const int max_s = kMaxParts / ts;
+    int S = splits_override;
+    if (S <= 0) {
+        const long groups = (long)p.B * pl.nblocks;
+        S = groups >= 256 ? 1 : (int)((256 + groups - 1) / groups);
+        const int by_len = p.n / 64 > 0 ? p.n / 64 : 1;
+        if (S > by_len) S = by_len;
+    }
+    if (S > max_s) S = max_s;
+    if (S < 1) S = 1;
+    pl.S = S;
+    pl.parts = S * ts;
+    return pl;
+}
+
+template <int DM, bool BF16>
+static hipError_t launch_core_t(const CoreArgs &a, int nrg, hipStream_t s)
+{
+    const int groups = a.B * a.S;
+    const dim3 grid(((groups + 7) / 8) * 8 * a.nblocks), block(256);
+    switch (nrg) {
+    case 1: hipLaunchKernelGGL((k_core_mfma<DM, BF16, 1>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_core_mfma<DM, BF16, 2>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((k_core_mfma<DM, BF16, 4>), grid, block, 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl,
+                          hipStream_t s)
+{
+    const dim3 grid((p.d_m + 255) / 256, pl.Rs, p.B), block(256);
+    if (p.dtype == EL_F16)
+        hipLaunchKernelGGL((k_elq_f16<f16_t>), grid, block, 0, s, (const float *)ws.Qp, (const f16_t *)ctx->w.Wk,
+                           (f16_t *)ws.ELQ, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
+    else
+        hipLaunchKernelGGL((k_elq_f16<bf16_t>), grid, block, 0, s, (const float *)ws.Qp, (const bf16_t *)ctx->w.Wk,
+                           (f16_t *)ws.ELQ, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
+    return hipGetLastError();
+}
+
+hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspace &ws, const CorePlan &pl,
+                            hipStream_t s)
+{
+    CoreArgs a;
+    a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
+    a.elq = (const f16_t *)ws.ELQ; a.Xp = ws.Xp; a.ML = ws.ML;
+    a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
+    const bool bf = p.dtype == EL_BF16;
+    if (p.d_m == 1024) return bf ? launch_core_t<1024, true>(a, pl.nrg, s) : launch_core_t<1024, false>(a, pl.nrg, s);
+    if (p.d_m == 512) return bf ? launch_core_t<512, true>(a, pl.nrg, s) : launch_core_t<512, false>(a, pl.nrg, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_merge_exp2(const el_attn_ctx *, const Problem &p, const Workspace &ws, const CorePlan &pl,
+                             hipStream_t s)
+{
+    hipLaunchKernelGGL(k_merge_exp2, dim3((p.d_m + 255) / 256, p.R, p.B), dim3(256), 0, s,
+                       (const float *)ws.Xp, (const float *)ws.ML, ws.Xn, p.d_m, p.R, pl.Rs, pl.parts);
+    return hipGetLastError();
+}
+
+} // namespace el

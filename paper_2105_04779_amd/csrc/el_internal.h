@@ -64,7 +64,7 @@ struct Weights {    // library-owned copies in the storage dtype, original layou
 struct el_attn_ctx {
     el_attn_config cfg;
     int hd;                 // heads * d_k
-    int Rpad_max;           // max_beam*heads rounded up to 16
+    int Rpad_max;           // max_beam*heads rounded up to a multiple of 64
     el::Weights w;
     void *ws_base;
     size_t ws_bytes;        // bound size
@@ -84,5 +84,19 @@ hipError_t launch_core_generic(const el_attn_ctx *ctx, const Problem &p, const W
 hipError_t launch_merge_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rstride, hipStream_t s);
 hipError_t launch_vproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
 hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
+
+// MFMA attention core -- core_mfma.hip
+struct CorePlan {
+    int nrg;      // 16-row groups per workgroup (1, 2 or 4)
+    int nblocks;  // row blocks (workgroups sharing one H range)
+    int Rs;       // padded row count of ELQ / partial buffers = nblocks * 16 * nrg
+    int S;        // contiguous key-range splits per batch element
+    int parts;    // partial results per (batch element, row) = S * 4 / nrg
+};
+bool core_mfma_supported(int dtype, int d_m);
+CorePlan plan_core_mfma(const Problem &p, int splits_override);
+hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
+hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
+hipError_t launch_merge_exp2(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 
 } // namespace el
