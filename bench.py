@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the EL-attention decode step on one MI355X.
+
+A "step" is one pass of the whole hot path (query projection and expansion, the
+attention core over H, value and output projections) over one batch of synthetic
+input already resident in HBM.  The step rotates over several H buffers whose
+total size exceeds the 256 MB memory-side cache, so every step streams its H from
+HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+ROTATE_BYTES = 768e6           # >= 3x the 256 MB memory-side cache
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c3_bart_large_bf16")
+    ap.add_argument("--splits", type=int, default=0, help="key-range splits (0 = automatic)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
+    ap.add_argument("--same-h", action="store_true", help="reuse one H buffer every step (cache-warm; not the reported protocol)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, wl, seconds):
+    """The fp64 oracle, as it stands, timed on this host on the first batch elements of the workload."""
+    import numpy as np
+    import oracle
+    W = wl.weights(w)
+    args = lambda H, Q, L: (H, L, Q, W["Wq"], W["bq"], W["Wk"], W["bk"], W["Wv"], W["bv"], W["Wo"], W["bo"])
+    threads = oracle.num_threads()
+    probe = min(w.B, max(1, threads))
+    H, Q, L = wl.batch(w, elements=range(probe))
+    t0 = time.perf_counter()
+    oracle.mha_reference(*args(H, Q, L), heads=w.heads, d_k=w.d_k)
+    t_probe = time.perf_counter() - t0
+    total = min(w.B, max(probe, int(probe * seconds / max(t_probe, 1e-3)) // probe * probe))
+    if total > probe:
+        H, Q, L = wl.batch(w, elements=range(total))
+        t0 = time.perf_counter()
+        oracle.mha_reference(*args(H, Q, L), heads=w.heads, d_k=w.d_k)
+        dt = time.perf_counter() - t0
+    else:
+        total, dt = probe, t_probe
+    return {
+        "value": total * w.beam / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {total} of {w.B} batch elements of {w.name} (their real lengths, sum {int(L.sum())}), "
+                  f"fp64 multi-head attention without cache, {dt:.2f} s",
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over batch elements with no "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2105_04779_amd import el_attn, traffic_model as tm, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[a.workload]
+    td = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
+
+    # ---- inputs, resident in HBM before anything is timed -----------------------------------
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import device_weights
+    W = wl.weights(w)
+    layer = el_attn.ElAttention(device_weights(W, w.dtype), heads=w.heads, d_k=w.d_k, dtype=w.dtype,
+                                max_batch=w.B, max_beam=w.beam, max_n=w.n)
+    if a.splits:
+        layer.set_splits(a.splits)
+    lens = wl.lengths(w)
+    Ld = torch.from_numpy(lens).cuda()
+    h_bytes = w.B * w.n * w.d_m * w.elem_bytes
+    nbuf = 1 if a.same_h else max(2, int(np.ceil(ROTATE_BYTES / h_bytes)))
+    g = torch.Generator(device="cuda").manual_seed(wl.BASE_SEED + w.index)
+    Hs = [torch.randn((w.B, w.n, w.d_m), generator=g, device="cuda", dtype=torch.float32).to(td) for _ in range(nbuf)]
+    Q = torch.randn((w.B, w.beam, w.d_m), generator=g, device="cuda", dtype=torch.float32).to(td)
+    out = torch.empty((w.B, w.beam, w.d_m), device="cuda", dtype=torch.float32)
+    torch.cuda.synchronize()
+
+    def run(steps, start=0):
+        for i in range(steps):
+            layer.decode_step(Hs[(start + i) % nbuf], Ld, Q, out=out)
+
+    # ---- whole-step throughput -------------------------------------------------------------
+    run(a.warmup)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    run(a.steps, a.warmup)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / a.steps
+    ev_ms_per_step = e0.elapsed_time(e1) / a.steps
+    assert torch.isfinite(out).all()
+
+    # ---- the dominant kernel (attention core) timed by itself, HIP events on its own stream ----
+    core_steps = min(a.steps, 1000)
+    layer.core_timing(core_steps)
+    run(core_steps, a.warmup + a.steps)
+    torch.cuda.synchronize()
+    core_ms = layer.read_core_timing(core_steps)
+    layer.core_timing(0)
+    core_avg_ms = float(np.mean(core_ms))
+
+    sum_len = int(lens.sum())
+    core_bytes = tm.core_algorithmic_bytes(sum_len, w.d_m, w.elem_bytes)
+    step_bytes = tm.step_algorithmic_bytes(sum_len, w.B, w.beam, w.d_m, w.heads * w.d_k, w.elem_bytes, 4)
+    achieved = core_bytes / (core_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f)
+
+    line = {
+        "metric": "decode-step queries/sec (B x beam)",
+        "value": w.B * w.beam / (ms_per_step * 1e-3),
+        "unit": "queries/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "beam": w.beam, "heads": w.heads, "d_m": w.d_m, "d_k": w.d_k,
+                   "n": w.n, "sum_len": sum_len, "h_buffers_rotated": nbuf, "mfma_path": layer.uses_mfma,
+                   "splits": a.splits},
+        "roofline": {"bound": "hbm", "kernel": "attention core (a3-a5)", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": core_bytes, "avg_launch_us": core_avg_ms * 1e3,
+                     "min_launch_us": float(np.min(core_ms)) * 1e3},
+        "step": {"algorithmic_bytes": step_bytes, "event_ms_per_step": ev_ms_per_step,
+                 "hbm_frac_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "flops": tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k),
+                 "tflops": tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k) / (ms_per_step * 1e-3) / 1e12},
+    }
+    if a.cpu_seconds > 0:
+        line["cpu_baseline"] = cpu_baseline(w, wl, a.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -156,8 +156,28 @@ el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq
 el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits);
 int32_t el_attn_max_splits(void);
 
+/*
+ * Second tuning knob, never semantics: how many 16-row groups of expanded queries one
+ * workgroup of the MFMA attention core owns (1, 2 or 4; 0 restores the automatic choice).
+ * With fewer rows per workgroup, several workgroups stream the same H range (served by
+ * the shared L2 after the first touch) and fewer key-range splits are needed.
+ */
+el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups);
+
 /* 1 if decode_step on this context runs the MFMA kernels, 0 if the generic fp32 ones. */
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);
+
+/*
+ * Measurement aid for callers that cannot see inside a step (the benchmark): once enabled
+ * with room for `max_steps` steps, every decode_step brackets its attention-core kernel
+ * (steps a3-a5) with a pair of HIP events on the stream it was given.  read() waits for the
+ * recorded events, writes the elapsed milliseconds of each step's core kernel to ms_out
+ * (at most `capacity`), stores the number written in *count and forgets them.  Steps beyond
+ * max_steps are not bracketed.  max_steps = 0 disables timing and releases the events.
+ * Errors: INVALID_ARG (null ctx/ms_out/count, negative sizes), ALLOC, HIP.
+ */
+el_status el_attn_core_timing_enable(el_attn_ctx *ctx, int32_t max_steps);
+el_status el_attn_core_timing_read(el_attn_ctx *ctx, float *ms_out, int32_t capacity, int32_t *count);
 
 /* Release the context and its packed weights (not the workspace, which the caller owns). */
 el_status el_attn_destroy(el_attn_ctx *ctx);

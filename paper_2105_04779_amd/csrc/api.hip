@@ -56,7 +56,7 @@ Workspace carve(const el_attn_ctx *c)
 
 void free_weights(el_attn_ctx *c)
 {
-    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, (void *)c->w.c_out};
+    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, c->w.WqT, c->w.WvT, c->w.WoT, (void *)c->w.c_out};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     std::memset(&c->w, 0, sizeof(c->w));
@@ -161,6 +161,18 @@ el_status el_attn_prepare(const el_attn_config *cfg,
         free_weights(c); delete c; return EL_ERR_ALLOC;
     }
     if (launch_cout(c, bv, bo, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+    c->use_mfma_gemm = (c->use_mfma_core && gemm_mfma_supported(cfg->dtype, cfg->d_model, cfg->d_k)) ? 1 : 0;
+    if (c->use_mfma_gemm) {
+        // transposed copies so that every MFMA operand fragment is contiguous along k
+        struct { void **dst; const void *src; int rows, cols; } tr[] = {
+            {&c->w.WqT, c->w.Wq, cfg->d_model, c->hd}, {&c->w.WvT, c->w.Wv, cfg->d_model, c->hd},
+            {&c->w.WoT, c->w.Wo, c->hd, cfg->d_model},
+        };
+        for (auto &t : tr) {
+            if (hipMalloc(t.dst, wbytes) != hipSuccess) { free_weights(c); delete c; return EL_ERR_ALLOC; }
+            if (launch_transpose16(t.src, *t.dst, t.rows, t.cols, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+        }
+    }
 
     *out_ctx = c;
     return EL_OK;
@@ -182,6 +194,13 @@ el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits)
 {
     if (!ctx || splits < 0 || splits > kMaxParts) return EL_ERR_INVALID_ARG;
     ctx->splits_override = splits;
+    return EL_OK;
+}
+
+el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups)
+{
+    if (!ctx || (row_groups != 0 && row_groups != 1 && row_groups != 2 && row_groups != 4)) return EL_ERR_INVALID_ARG;
+    ctx->nrg_override = row_groups;
     return EL_OK;
 }
 
@@ -220,18 +239,43 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
 
-    // a1
-    if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
     if (el_attn_uses_mfma(ctx)) {
-        // a2 in fp16 for the MFMA core, a3-a5 on MFMA, merge of the key-range partials
-        const CorePlan pl = plan_core_mfma(p, ctx->splits_override);
-        if (launch_elq_f16(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override);
+        // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
+        const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
+        if (ctx->use_mfma_gemm) {
+            if (launch_qproj_mfma(ctx, p, ws, qscale, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_elq_mfma(ctx, p, ws, pl.Rs, s) != hipSuccess) return EL_ERR_HIP;
+        } else {
+            if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_elq_f16(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        }
+        // a3-a5 on MFMA; key-range partials
+        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
+        if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
         if (launch_core_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        if (timed) {
+            if (hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], s) != hipSuccess) return EL_ERR_HIP;
+            ctx->ev_used++;
+        }
+        if (ctx->use_mfma_gemm) {
+            // merge of the partials fused into a6, then a7
+            if (launch_vproj_mfma(ctx, p, ws, pl.parts, pl.Rs, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_oproj_mfma(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+            return EL_OK;
+        }
         if (launch_merge_exp2(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
     } else {
+        if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
         if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
         const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
+        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
+        if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
         if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
+        if (timed) {
+            if (hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], s) != hipSuccess) return EL_ERR_HIP;
+            ctx->ev_used++;
+        }
         if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
     }
     // a6, a7
@@ -240,9 +284,48 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
     return EL_OK;
 }
 
+static void free_events(el_attn_ctx *ctx)
+{
+    if (ctx->ev) {
+        for (int i = 0; i < 2 * ctx->ev_cap; ++i)
+            if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+        std::free(ctx->ev);
+    }
+    ctx->ev = nullptr;
+    ctx->ev_cap = ctx->ev_used = 0;
+}
+
+el_status el_attn_core_timing_enable(el_attn_ctx *ctx, int32_t max_steps)
+{
+    if (!ctx || max_steps < 0 || max_steps > (1 << 20)) return EL_ERR_INVALID_ARG;
+    free_events(ctx);
+    if (max_steps == 0) return EL_OK;
+    ctx->ev = (hipEvent_t *)std::calloc((size_t)2 * max_steps, sizeof(hipEvent_t));
+    if (!ctx->ev) return EL_ERR_ALLOC;
+    ctx->ev_cap = max_steps;
+    for (int i = 0; i < 2 * max_steps; ++i)
+        if (hipEventCreate(&ctx->ev[i]) != hipSuccess) { free_events(ctx); return EL_ERR_HIP; }
+    return EL_OK;
+}
+
+el_status el_attn_core_timing_read(el_attn_ctx *ctx, float *ms_out, int32_t capacity, int32_t *count)
+{
+    if (!ctx || !ms_out || !count || capacity < 0) return EL_ERR_INVALID_ARG;
+    *count = 0;
+    const int n = ctx->ev_used < capacity ? ctx->ev_used : capacity;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(ctx->ev[2 * i + 1]) != hipSuccess) return EL_ERR_HIP;
+        if (hipEventElapsedTime(&ms_out[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]) != hipSuccess) return EL_ERR_HIP;
+    }
+    *count = n;
+    ctx->ev_used = 0;
+    return EL_OK;
+}
+
 el_status el_attn_destroy(el_attn_ctx *ctx)
 {
     if (!ctx) return EL_ERR_INVALID_ARG;
+    free_events(ctx);
     free_weights(ctx);
     delete ctx;
     return EL_OK;

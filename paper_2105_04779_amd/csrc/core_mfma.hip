@@ -43,6 +43,9 @@ struct CoreArgs {
     float *Xp;               // [B, parts, Rs, DM]
     float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
     int n, B, R, Rs, S, nblocks;
+#ifdef EL_CORE_PROF
+    unsigned long long *prof;   // per-phase cycle totals of workgroup 0, wave 0 (debug builds only)
+#endif
 };
 
 // 16-byte chunk swizzle inside a tile row: a bijection of the low four chunk bits that makes both
@@ -56,22 +59,46 @@ __device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x)
     return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
+#ifdef EL_CORE_PROF
+#define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define EL_PROF(i) { const unsigned long long now = clock64(); prof_acc[i] += now - prof_t; prof_t = now; }
+#else
+#define EL_PROF_DECL
+#define EL_PROF(i)
+#endif
+
+// One 1 KB piece of a tile row, fetched by one wavefront straight into LDS.  `lds_addr` is the
+// LDS byte address the piece starts at (lane i lands at +16 i), `voff` the lane's byte offset from
+// the wave-uniform global base.  Issued through inline assembly so that the compiler does not
+// serialise later LDS reads of the *other* tile buffer behind it; completion is awaited
+// explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma_piece(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
 template <int DM, bool BF16, int NRG>
 __global__ void __launch_bounds__(256)
 k_core_mfma(const CoreArgs a)
 {
-    constexpr int ROWB = DM * 2;                  // bytes per tile row in LDS (fp16)
-    constexpr int CPR = DM / 8;                   // 16-byte chunks per row
+    constexpr int ROWB = DM * 2;                  // bytes per tile row (2-byte elements)
     constexpr int TILE_BYTES = kTileRows * ROWB;
-    constexpr int DMA_PER_WAVE = TILE_BYTES / 1024 / 4;
-    constexpr int CHUNKS_PER_THREAD = kTileRows * CPR / 256;
+    constexpr int PIECES_PER_ROW = ROWB / 1024;   // 1 KB LDS-DMA pieces per row (1 or 2)
+    constexpr int CHUNKS_PER_THREAD = TILE_BYTES / 16 / 256;
     constexpr int KCH = DM / 32;                  // k-chunks of the score product
     constexpr int DB = DM / 16;                   // 16-column blocks of the output
     constexpr int TS = 4 / NRG;                   // wavefronts sharing a row group (tile parities)
-    static_assert(CPR % 64 == 0, "a 1 KB LDS-DMA piece must not straddle tile rows");
+    static_assert(ROWB % 1024 == 0 && PIECES_PER_ROW <= 2, "rows are fetched as one or two 1 KB pieces");
 
-    __shared__ __attribute__((aligned(1024))) char F[TILE_BYTES]; // fp16 tile, swizzled, MFMA operand source
-    __shared__ __attribute__((aligned(1024))) char Rw[TILE_BYTES]; // raw landing zone of the next tile
+    // Two tile buffers.  A tile lands raw (storage dtype) in swizzled order, is converted to fp16 in
+    // place when the storage type is bf16, and is then read by the MFMA phases.
+    __shared__ __attribute__((aligned(1024))) char T[2 * TILE_BYTES];
 
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -103,9 +130,11 @@ k_core_mfma(const CoreArgs a)
     // ---- ELQ rows of this wavefront: B operand of the score product ------------------------
     h8 elq[KCH];
     {
+        // pad rows (row >= R) are never written by the expansion step: they read as zero here
         const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + 8 * g;
+        const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < KCH; ++c) elq[c] = *(const h8 *)(src + 32 * c);
+        for (int c = 0; c < KCH; ++c) elq[c] = row < a.R ? *(const h8 *)(src + 32 * c) : zero;
     }
 
     f4 X[DB];
@@ -113,8 +142,9 @@ k_core_mfma(const CoreArgs a)
     for (int i = 0; i < DB; ++i) X[i] = f4{0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, l_sum = 0.f;
 
-    // ---- per-lane LDS addresses -------------------------------------------------------------
-    const EL_LDS(char) *Fl = (const EL_LDS(char) *)F;
+    // ---- per-lane LDS offsets inside a tile buffer -----------------------------------------
+    const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
+    const unsigned t_lds = (unsigned)(uintptr_t)Tl;
     int a_base[4]; // score product: row r16 (+16), chunk 4c+g
     {
         const int fx = row_swizzle(r16), cx = fx >> 2, gx = g ^ (fx & 3);
@@ -129,77 +159,74 @@ k_core_mfma(const CoreArgs a)
             b_base[di] = t_lo * ROWB + ((((2 * di) + (q >> 1)) ^ ft) << 4) + (q & 1) * 8;
     }
 
-    auto issue_dma = [&](int kt) {
+    // Fetch tile kt into the buffer at byte offset `buf`.  Wavefront w brings rows 8w..8w+7; lane i of
+    // a piece lands at physical chunk i and therefore fetches logical chunk i ^ swizzle(row), so the
+    // tile arrives already in the bank-friendly order the MFMA phases read (a permutation inside
+    // one 256-byte span: the global access stays fully coalesced).  Rows at or beyond len are not read.
+    auto issue_dma = [&](int kt, unsigned buf) {
+        const char *sbase = Hb + ((size_t)kt * kTileRows + 8 * w) * ROWB;
+        const int rows_valid = len - (kt * kTileRows + 8 * w);      // wave-uniform
 #pragma unroll
-        for (int i = 0; i < DMA_PER_WAVE; ++i) {
-            const int piece = w * DMA_PER_WAVE + i;          // 1 KB piece of the tile
-            const int trow = (piece * 64) / CPR;
-            const int cc = (piece * 64) % CPR + l;
-            const int t = kt * kTileRows + trow;
-            if (t < len)
-                __builtin_amdgcn_global_load_lds(
-                    (const EL_GLOBAL(void) *)(Hb + ((size_t)t * DM + (size_t)cc * 8) * 2),
-                    (EL_LDS(void) *)(Rw + piece * 1024), 16, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+            const int f = (i << 1) | (w & 1);                        // row_swizzle(8w + i)
+            const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
+            const unsigned dst = t_lds + buf + (8 * w + i) * ROWB;
+            if (i < rows_valid) {
+                if (PIECES_PER_ROW == 2) dma_row_2k(dst, voff, sbase);
+                else dma_piece(dst, voff, sbase);
+            }
         }
     };
 
-    auto convert_chunk = [&](u4 v) {
-        if (BF16) {
-            v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
-            v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
-        }
-        return v;
-    };
-    // Raw tile -> fp16 tile in MFMA-friendly (swizzled) order.  Rows at or beyond len are written
-    // as zeros and their landing-zone bytes are never read.
-    auto convert_tile = [&](int kt) {
-        int tid = threadIdx.x;
-        asm volatile("" : "+v"(tid));           // recompute the LDS addresses per tile instead of
-                                                // keeping 2 x CHUNKS_PER_THREAD of them in registers
-        if ((kt + 1) * kTileRows <= len) {        // full tile: no per-row checks, reads batched
-            constexpr int BATCH = 4;
+    // Storage dtype -> fp16 in place (bf16 only), zero-fill of rows at or beyond len (ragged last
+    // tile: their bytes were never fetched and must not reach the MFMAs as garbage).
+    auto convert_tile = [&](int kt, unsigned buf) {
+        const bool full = (kt + 1) * kTileRows <= len;
+        if (!BF16 && full) return;
+        char *base = T + buf + tid * 16;
 #pragma unroll
-            for (int i0 = 0; i0 < CHUNKS_PER_THREAD; i0 += BATCH) {
-                u4 v[BATCH];
+        for (int i0 = 0; i0 < CHUNKS_PER_THREAD; i0 += 4) {
+            u4 v[4];
 #pragma unroll
-                for (int e = 0; e < BATCH; ++e) v[e] = *(const u4 *)(Rw + ((i0 + e) * 256 + tid) * 16);
+            for (int e = 0; e < 4; ++e) v[e] = *(const u4 *)(base + (i0 + e) * 4096);
 #pragma unroll
-                for (int e = 0; e < BATCH; ++e) {
-                    const int idc = (i0 + e) * 256 + tid;
-                    const int trow = idc / CPR, cc = idc % CPR;
-                    *(u4 *)(F + trow * ROWB + ((cc ^ row_swizzle(trow)) << 4)) = convert_chunk(v[e]);
+            for (int e = 0; e < 4; ++e) {
+                if (BF16) {
+                    v[e].x = bf16x2_to_f16x2(v[e].x); v[e].y = bf16x2_to_f16x2(v[e].y);
+                    v[e].z = bf16x2_to_f16x2(v[e].z); v[e].w = bf16x2_to_f16x2(v[e].w);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
-                const int idc = i * 256 + tid;
-                const int trow = idc / CPR, cc = idc % CPR;
-                const int t = kt * kTileRows + trow;
-                u4 v = u4{0u, 0u, 0u, 0u};
-                if (t < len) v = convert_chunk(*(const u4 *)(Rw + idc * 16));
-                *(u4 *)(F + trow * ROWB + ((cc ^ row_swizzle(trow)) << 4)) = v;
+                if (!full) {
+                    const int trow = ((i0 + e) * 4096 + tid * 16) / ROWB;
+                    if (kt * kTileRows + trow >= len) v[e] = u4{0u, 0u, 0u, 0u};
+                }
+                *(u4 *)(base + (i0 + e) * 4096) = v[e];
             }
         }
     };
 
-    if (nloc > 0) issue_dma(k0);
+    EL_PROF_DECL
+    if (nloc > 0) {
+        issue_dma(k0, 0);
+        if (nloc > 1) issue_dma(k0 + 1, TILE_BYTES);
+        // tile k0 must have landed; the fetches of tile k0+1 (issued later, completing in order) may still fly
+        // (only when that tile is full, so that this wavefront issued exactly 8 rows of it)
+        if (nloc > 1 && (k0 + 2) * kTileRows <= len) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(8 * PIECES_PER_ROW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        convert_tile(k0, 0);
+        __syncthreads();
+    }
+    EL_PROF(0)
 
     for (int kk = 0; kk < nloc; ++kk) {
         const int kt = k0 + kk;
-        // Every wavefront drains its own LDS-DMA before the barrier: the conversion pass reads
-        // pieces that other wavefronts fetched, and the compiler only orders a wave's own accesses.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();            // tile kt has landed in Rw; all reads of F are done
-        convert_tile(kt);
-        __syncthreads();            // F holds tile kt; Rw is free
-        if (kk + 1 < nloc) issue_dma(kt + 1);
-        if (TS > 1 && (kk % TS) != tsel) continue;
+        const unsigned cur = (kk & 1) * TILE_BYTES, nxt = TILE_BYTES - cur;
+        const EL_LDS(char) *Fl = Tl + cur;
 
+        if (TS == 1 || (kk % TS) == tsel) {
         // ---- scores: S^T[t, r] for the 32 rows of the tile --------------------------------
-        // Software-pipelined by hand in groups of four k-chunks: the LDS reads of group cc+1 are
-        // issued before the MFMAs of group cc; the scheduling barriers keep the compiler from
+        // Software-pipelined by hand in groups of two k-chunks: the LDS reads of the next group are
+        // issued before the MFMAs of this one; the scheduling barriers keep the compiler from
         // hoisting every read to the top (which would spill the accumulators).
         f4 s0a = {0.f, 0.f, 0.f, 0.f}, s0b = s0a, s1a = s0a, s1b = s0a;
         {
@@ -225,6 +252,7 @@ k_core_mfma(const CoreArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        EL_PROF(5)
         float sc[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) { sc[j] = s0a[j] + s0b[j]; sc[4 + j] = s1a[j] + s1b[j]; }
@@ -270,9 +298,10 @@ k_core_mfma(const CoreArgs a)
             const h2 p67 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[6], pr[7]));
             P = h8{p01[0], p01[1], p23[0], p23[1], p45[0], p45[1], p67[0], p67[1]};
         }
+        EL_PROF(6)
 
         // ---- weighted sum: X^T[d, r] += sum_t H[t, d] P[r, t] ----------------------------------
-        // Same hand pipelining, in groups of eight 16-column blocks (16 transposing reads each).
+        // Same hand pipelining, in groups of four 16-column blocks (8 transposing reads each).
         {
             typedef short s8 __attribute__((ext_vector_type(8)));
             s4 tb[2][8];
@@ -299,11 +328,30 @@ k_core_mfma(const CoreArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        EL_PROF(7)
+        }
+
+        // Tile kt+1 was requested a whole period ago: drain this wavefront's share, then meet the others.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();            // every wave is done reading `cur`; tile kt+1 has landed in `nxt`
+        EL_PROF(1)
+        if (kk + 2 < nloc) issue_dma(kt + 2, cur);      // flies during the conversion and the next tile's MFMAs
+        EL_PROF(4)
+        if (kk + 1 < nloc) convert_tile(kt + 1, nxt);
+        EL_PROF(2)
+        __syncthreads();            // `nxt` is ready for the MFMA phases
+        EL_PROF(3)
     }
 
     // ---- partial result of this wavefront -----------------------------------------------------
     l_sum += __shfl_xor(l_sum, 16, 64);
     l_sum += __shfl_xor(l_sum, 32, 64);
+#ifdef EL_CORE_PROF
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
+        for (int i = 0; i < 8; ++i) a.prof[i] = prof_acc[i];
+        a.prof[8] = (unsigned long long)nloc;
+    }
+#endif
     if (row < a.R) {
         if (g == 0) { ml_out[0] = m_ref; ml_out[1] = l_sum; }
         if (l_sum > 0.f) {
@@ -324,7 +372,7 @@ __global__ void k_elq_f16(const float *__restrict__ Qp, const T *__restrict__ Wk
     if (d >= d_m) return;
     float acc = 0.f;
     if (r < R) {
-        const int i = r / beam, j = r % beam;
+        const int i = r / beam, j = r % beam;   // Qp carries 1/sqrt(d_k) only on this path
         const float *qp = Qp + ((size_t)b * beam + j) * hd + (size_t)i * d_k;
         const T *wk = Wk + (size_t)d * hd + (size_t)i * d_k;
         for (int c = 0; c < d_k; ++c) acc = fmaf(qp[c], to_f32(wk[c]), acc);
@@ -358,18 +406,24 @@ __global__ void k_merge_exp2(const float *__restrict__ Xp, const float *__restri
     Xn[((size_t)b * R + r) * d_m + d] = num / den;
 }
 
+#ifdef EL_CORE_PROF
+static unsigned long long *g_core_prof = nullptr;
+extern "C" void el_attn_debug_set_prof(unsigned long long *p) { g_core_prof = p; }
+#endif
+
 // ---------------------------------------------------------------------------------------------
 bool core_mfma_supported(int dtype, int d_m)
 {
     return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024);
 }
 
-CorePlan plan_core_mfma(const Problem &p, int splits_override)
+CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override)
 {
     CorePlan pl;
     if (p.R <= 16) pl.nrg = 1;
     else if (p.R <= 32) pl.nrg = 2;
     else pl.nrg = 4;
+    if (nrg_override > 0 && nrg_override < pl.nrg) pl.nrg = nrg_override;
     pl.nblocks = (p.R + 16 * pl.nrg - 1) / (16 * pl.nrg);
     pl.Rs = pl.nblocks * 16 * pl.nrg;
     const int ts = 4 / pl.nrg;
@@ -421,6 +475,9 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
     a.elq = (const f16_t *)ws.ELQ; a.Xp = ws.Xp; a.ML = ws.ML;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
+#ifdef EL_CORE_PROF
+    a.prof = g_core_prof;
+#endif
     const bool bf = p.dtype == EL_BF16;
     if (p.d_m == 1024) return bf ? launch_core_t<1024, true>(a, pl.nrg, s) : launch_core_t<1024, false>(a, pl.nrg, s);
     if (p.d_m == 512) return bf ? launch_core_t<512, true>(a, pl.nrg, s) : launch_core_t<512, false>(a, pl.nrg, s);

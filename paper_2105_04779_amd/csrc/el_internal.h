@@ -53,9 +53,10 @@ struct Workspace {
     float *A;       // [B*beam, hd]                 a6 result, fp32
 };
 
-struct Weights {    // library-owned copies in the storage dtype, original layout
-    void *Wq, *Wk, *Wv, *Wo, *bq;
-    float *c_out;   // [d_m] = b_o + b_v . W_o, fp32
+struct Weights {    // library-owned copies in the storage dtype
+    void *Wq, *Wk, *Wv, *Wo, *bq;   // original layout (x . W form)
+    void *WqT, *WvT, *WoT;          // transposed copies for the MFMA GEMMs (16-bit dtypes only)
+    float *c_out;                   // [d_m] = b_o + b_v . W_o, fp32
 };
 
 } // namespace el
@@ -70,8 +71,13 @@ struct el_attn_ctx {
     size_t ws_bytes;        // bound size
     size_t ws_need;         // required size
     int splits_override;    // 0 = automatic
+    int nrg_override;       // 0 = automatic
     int use_mfma_core;      // MFMA attention core available for this (dtype, d_m)
+    int use_mfma_gemm;      // MFMA projection GEMMs available for this (dtype, d_m, d_k)
     int device;
+    // optional event pairs around the core kernel (measurement aid)
+    hipEvent_t *ev;         // 2 * ev_cap events, or null
+    int ev_cap, ev_used;
 };
 
 namespace el {
@@ -94,9 +100,17 @@ struct CorePlan {
     int parts;    // partial results per (batch element, row) = S * 4 / nrg
 };
 bool core_mfma_supported(int dtype, int d_m);
-CorePlan plan_core_mfma(const Problem &p, int splits_override);
+CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override);
 hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_merge_exp2(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
+
+// MFMA projection GEMMs -- gemm_mfma.hip
+bool gemm_mfma_supported(int dtype, int d_m, int d_k);
+hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hipStream_t s);
+hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, float scale, hipStream_t s);
+hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s);
+hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs, hipStream_t s);
+hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
 
 } // namespace el

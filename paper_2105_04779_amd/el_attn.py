@@ -20,7 +20,9 @@ DTYPE_CODES = {"f32": EL_F32, "f16": EL_F16, "bf16": EL_BF16}
 
 EXPORTED_SYMBOLS = (
     "el_attn_prepare", "el_attn_workspace_bytes", "el_attn_bind_workspace", "el_attn_decode_step",
-    "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_uses_mfma",
+    "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
+    "el_attn_uses_mfma",
+    "el_attn_core_timing_enable", "el_attn_core_timing_read",
     "el_attn_destroy", "el_attn_status_string", "el_attn_version",
 )
 
@@ -59,10 +61,16 @@ def _load():
     lib.el_attn_expand_query.restype = ctypes.c_int
     lib.el_attn_set_splits.argtypes = [vp, i32]
     lib.el_attn_set_splits.restype = ctypes.c_int
+    lib.el_attn_set_row_groups.argtypes = [vp, i32]
+    lib.el_attn_set_row_groups.restype = ctypes.c_int
     lib.el_attn_max_splits.argtypes = []
     lib.el_attn_max_splits.restype = i32
     lib.el_attn_uses_mfma.argtypes = [vp]
     lib.el_attn_uses_mfma.restype = i32
+    lib.el_attn_core_timing_enable.argtypes = [vp, i32]
+    lib.el_attn_core_timing_enable.restype = ctypes.c_int
+    lib.el_attn_core_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
+    lib.el_attn_core_timing_read.restype = ctypes.c_int
     lib.el_attn_destroy.argtypes = [vp]
     lib.el_attn_destroy.restype = ctypes.c_int
     lib.el_attn_status_string.argtypes = [ctypes.c_int]
@@ -118,8 +126,24 @@ def el_attn_set_splits(ctx, splits) -> int:
     return lib.el_attn_set_splits(ctx, splits)
 
 
+def el_attn_set_row_groups(ctx, row_groups) -> int:
+    return lib.el_attn_set_row_groups(ctx, row_groups)
+
+
 def el_attn_uses_mfma(ctx) -> int:
     return int(lib.el_attn_uses_mfma(ctx))
+
+
+def el_attn_core_timing_enable(ctx, max_steps) -> int:
+    return lib.el_attn_core_timing_enable(ctx, max_steps)
+
+
+def el_attn_core_timing_read(ctx, capacity):
+    """Returns (status, [milliseconds of each recorded step's core kernel])."""
+    buf = (ctypes.c_float * max(capacity, 1))()
+    n = ctypes.c_int32(0)
+    st = lib.el_attn_core_timing_read(ctx, buf, capacity, ctypes.byref(n))
+    return st, [buf[i] for i in range(n.value)]
 
 
 def el_attn_destroy(ctx) -> int:
@@ -182,6 +206,11 @@ class ElAttention:
         if st != EL_OK:
             raise ElAttnError(st, "el_attn_set_splits")
 
+    def set_row_groups(self, row_groups: int):
+        st = el_attn_set_row_groups(self.ctx, row_groups)
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_set_row_groups")
+
     def decode_step(self, H, lengths, queries, out=None):
         """H [B,n,d_m] (batch stride free, rows contiguous), lengths int32 [B] or None,
         queries [B,beam,d_m] contiguous.  Returns out [B,beam,d_m]."""
@@ -201,6 +230,17 @@ class ElAttention:
         if st != EL_OK:
             raise ElAttnError(st, "el_attn_decode_step")
         return out
+
+    def core_timing(self, max_steps: int):
+        st = el_attn_core_timing_enable(self.ctx, max_steps)
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_core_timing_enable")
+
+    def read_core_timing(self, capacity: int):
+        st, ms = el_attn_core_timing_read(self.ctx, capacity)
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_core_timing_read")
+        return ms
 
     def expand_query(self, queries):
         torch = self._torch

@@ -68,7 +68,10 @@ def test_null_context_is_rejected_everywhere(ea):
     assert ea.el_attn_decode_step(None, FAKE, 64, None, FAKE, FAKE, 1, 1, 1) == I
     assert ea.el_attn_expand_query(None, FAKE, FAKE, 1, 1) == I
     assert ea.el_attn_set_splits(None, 1) == I
+    assert ea.el_attn_set_row_groups(None, 1) == I
     assert ea.el_attn_uses_mfma(None) == 0
+    assert ea.el_attn_core_timing_enable(None, 4) == I
+    assert ea.el_attn_core_timing_read(None, 4)[0] == I
     assert ea.el_attn_destroy(None) == I
 
 
