@@ -40,7 +40,7 @@ struct CoreArgs {
     int64_t h_stride;        // elements between batch elements
     const int32_t *lengths;
     const f16_t *elq;        // [B, Rs, DM] fp16, scaled by log2(e)/sqrt(d_k), pad rows zero
-    float *Xp;               // [B, parts, Rs, DM]
+    f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
     float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
     int n, B, R, Rs, S, nblocks;
 #ifdef EL_CORE_PROF
@@ -123,7 +123,6 @@ k_core_mfma(const CoreArgs a)
 
     const int parts = a.S * TS, part = s * TS + tsel;
     float *ml_out = a.ML + (((size_t)b * parts + part) * a.Rs + row) * 2;
-    float *x_out = a.Xp + (((size_t)b * parts + part) * a.Rs + row) * DM;
 
     const char *Hb = (const char *)a.H + (size_t)b * a.h_stride * 2;
 
@@ -159,15 +158,17 @@ k_core_mfma(const CoreArgs a)
             b_base[di] = t_lo * ROWB + ((((2 * di) + (q >> 1)) ^ ft) << 4) + (q & 1) * 8;
     }
 
-    // Fetch tile kt into the buffer at byte offset `buf`.  Wavefront w brings rows 8w..8w+7; lane i of
-    // a piece lands at physical chunk i and therefore fetches logical chunk i ^ swizzle(row), so the
-    // tile arrives already in the bank-friendly order the MFMA phases read (a permutation inside
-    // one 256-byte span: the global access stays fully coalesced).  Rows at or beyond len are not read.
-    auto issue_dma = [&](int kt, unsigned buf) {
+    // Fetch rows [i_begin, i_end) of this wavefront's share (rows 8w..8w+7) of tile kt into the buffer at
+    // byte offset `buf`.  Lane i of a piece lands at physical chunk i and therefore fetches logical
+    // chunk i ^ swizzle(row), so the tile arrives already in the bank-friendly order the MFMA phases
+    // read (a permutation inside one 256-byte span: the global access stays fully coalesced).
+    // Rows at or beyond len are not read.
+    auto issue_dma_rows = [&](int kt, unsigned buf, int i_begin, int i_end) {
         const char *sbase = Hb + ((size_t)kt * kTileRows + 8 * w) * ROWB;
         const int rows_valid = len - (kt * kTileRows + 8 * w);      // wave-uniform
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if (i < i_begin || i >= i_end) continue;
             const int f = (i << 1) | (w & 1);                        // row_swizzle(8w + i)
             const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
             const unsigned dst = t_lds + buf + (8 * w + i) * ROWB;
@@ -177,29 +178,43 @@ k_core_mfma(const CoreArgs a)
             }
         }
     };
+    auto issue_dma = [&](int kt, unsigned buf) { issue_dma_rows(kt, buf, 0, 8); };
 
-    // Storage dtype -> fp16 in place (bf16 only), zero-fill of rows at or beyond len (ragged last
-    // tile: their bytes were never fetched and must not reach the MFMAs as garbage).
-    auto convert_tile = [&](int kt, unsigned buf) {
-        const bool full = (kt + 1) * kTileRows <= len;
-        if (!BF16 && full) return;
-        char *base = T + buf + tid * 16;
+    // Storage dtype -> fp16 in place (bf16 only) for tile kt_conv in `cbuf`, zero-fill of its rows at or
+    // beyond len (ragged last tile: their bytes were never fetched and must not reach the MFMAs as
+    // garbage), interleaved with the fetch requests of tile kt_dma into `dbuf`: the requests stall at
+    // issue when the memory pipeline is busy, and that time is spent waiting for LDS data anyway.
+    auto stage = [&](bool do_conv, int kt_conv, unsigned cbuf, bool do_dma, int kt_dma, unsigned dbuf) {
+        const bool full = (kt_conv + 1) * kTileRows <= len;
+        if (!do_conv || (!BF16 && full)) {
+            if (do_dma) issue_dma(kt_dma, dbuf);
+            return;
+        }
+        constexpr int NB = CHUNKS_PER_THREAD / 4;     // batches of four 16-byte chunks per thread
+        constexpr int RPB = 8 / NB;                   // fetch rows issued per batch
+        char *base = T + cbuf + tid * 16;
+        u4 v[2][4];
 #pragma unroll
-        for (int i0 = 0; i0 < CHUNKS_PER_THREAD; i0 += 4) {
-            u4 v[4];
+        for (int e = 0; e < 4; ++e) v[0][e] = *(const u4 *)(base + e * 4096);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = *(const u4 *)(base + (i0 + e) * 4096);
+        for (int bi = 0; bi < NB; ++bi) {
+            if (bi + 1 < NB) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[(bi + 1) & 1][e] = *(const u4 *)(base + (4 * (bi + 1) + e) * 4096);
+            }
+            if (do_dma) issue_dma_rows(kt_dma, dbuf, bi * RPB, (bi + 1) * RPB);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
+                u4 x = v[bi & 1][e];
                 if (BF16) {
-                    v[e].x = bf16x2_to_f16x2(v[e].x); v[e].y = bf16x2_to_f16x2(v[e].y);
-                    v[e].z = bf16x2_to_f16x2(v[e].z); v[e].w = bf16x2_to_f16x2(v[e].w);
+                    x.x = bf16x2_to_f16x2(x.x); x.y = bf16x2_to_f16x2(x.y);
+                    x.z = bf16x2_to_f16x2(x.z); x.w = bf16x2_to_f16x2(x.w);
                 }
                 if (!full) {
-                    const int trow = ((i0 + e) * 4096 + tid * 16) / ROWB;
-                    if (kt * kTileRows + trow >= len) v[e] = u4{0u, 0u, 0u, 0u};
+                    const int trow = ((4 * bi + e) * 4096 + tid * 16) / ROWB;
+                    if (kt_conv * kTileRows + trow >= len) x = u4{0u, 0u, 0u, 0u};
                 }
-                *(u4 *)(base + (i0 + e) * 4096) = v[e];
+                *(u4 *)(base + (4 * bi + e) * 4096) = x;
             }
         }
     };
@@ -213,7 +228,7 @@ k_core_mfma(const CoreArgs a)
         if (nloc > 1 && (k0 + 2) * kTileRows <= len) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(8 * PIECES_PER_ROW) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        convert_tile(k0, 0);
+        stage(true, k0, 0, false, 0, 0);
         __syncthreads();
     }
     EL_PROF(0)
@@ -290,12 +305,11 @@ k_core_mfma(const CoreArgs a)
 #pragma unroll
         for (int j = 0; j < 8; ++j) { pr[j] = __builtin_amdgcn_exp2f(sc[j] - m_ref); psum += pr[j]; }
         l_sum += psum;
-        h8 P;
+        h8 P;   // round-to-nearest-even: an unbiased P keeps sum(P) and the weighted sum consistent
         {
-            const h2 p01 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[0], pr[1]));
-            const h2 p23 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[2], pr[3]));
-            const h2 p45 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[4], pr[5]));
-            const h2 p67 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pr[6], pr[7]));
+            typedef float f2 __attribute__((ext_vector_type(2)));
+            const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
+            const h2 p45 = __builtin_convertvector(f2{pr[4], pr[5]}, h2), p67 = __builtin_convertvector(f2{pr[6], pr[7]}, h2);
             P = h8{p01[0], p01[1], p23[0], p23[1], p45[0], p45[1], p67[0], p67[1]};
         }
         EL_PROF(6)
@@ -335,9 +349,9 @@ k_core_mfma(const CoreArgs a)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();            // every wave is done reading `cur`; tile kt+1 has landed in `nxt`
         EL_PROF(1)
-        if (kk + 2 < nloc) issue_dma(kt + 2, cur);      // flies during the conversion and the next tile's MFMAs
-        EL_PROF(4)
-        if (kk + 1 < nloc) convert_tile(kt + 1, nxt);
+        // tile kt+2 is requested into `cur` (it flies during this conversion and the next tile's MFMAs)
+        // while tile kt+1 is converted in `nxt`
+        stage(kk + 1 < nloc, kt + 1, nxt, kk + 2 < nloc, kt + 2, cur);
         EL_PROF(2)
         __syncthreads();            // `nxt` is ready for the MFMA phases
         EL_PROF(3)
@@ -352,11 +366,38 @@ k_core_mfma(const CoreArgs a)
         a.prof[8] = (unsigned long long)nloc;
     }
 #endif
-    if (row < a.R) {
-        if (g == 0) { ml_out[0] = m_ref; ml_out[1] = l_sum; }
-        if (l_sum > 0.f) {
+    if (row < a.R && g == 0) { ml_out[0] = m_ref; ml_out[1] = l_sum; }
+
+    // The partial goes out normalised by its own sum, in fp16 (|x| <= max|H|; 2^-12 relative rounding,
+    // far inside the error budget) and through LDS so that every global store instruction writes
+    // 1 KB of one row: the partials are the largest write stream of the step.
+    __syncthreads();                                   // all wavefronts are done with the tile buffers
+    const bool had_tiles = TS == 1 ? nloc > 0 : nloc > tsel;
+    if (had_tiles) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        const float inv = 1.0f / l_sum;
+        char *E = T + w * (16 * ROWB);                 // this wavefront's 16 x DM fp16 staging area
+        // 8-byte units of a row are XOR-swizzled with the row number to spread the banks
 #pragma unroll
-            for (int db = 0; db < DB; ++db) *(f4 *)(x_out + 16 * db + 4 * g) = X[db];
+        for (int db = 0; db < DB; ++db) {
+            const f4 x = X[db];
+            const h2 lo = __builtin_convertvector(f2{x[0] * inv, x[1] * inv}, h2);
+            const h2 hi = __builtin_convertvector(f2{x[2] * inv, x[3] * inv}, h2);
+            *(h4 *)(E + r16 * ROWB + (((4 * db + g) ^ r16) << 3)) = h4{lo[0], lo[1], hi[0], hi[1]};
+        }
+        const int row0 = rb * (16 * NRG) + 16 * rg;
+        f16_t *x_out = a.Xp + (((size_t)b * parts + part) * a.Rs + row0) * DM;
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) {
+#pragma unroll
+            for (int hf = 0; hf < DM / 512; ++hf) {
+                if (row0 + rr >= a.R) continue;
+                const int u0 = hf * 128 + 2 * l;
+                const h4 v0 = *(const h4 *)(E + rr * ROWB + ((u0 ^ rr) << 3));
+                const h4 v1 = *(const h4 *)(E + rr * ROWB + (((u0 + 1) ^ rr) << 3));
+                *(h8 *)(x_out + (size_t)rr * DM + hf * 512 + 8 * l) = h8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+            }
         }
     }
 }
@@ -381,8 +422,9 @@ __global__ void k_elq_f16(const float *__restrict__ Qp, const T *__restrict__ Wk
     elq[((size_t)b * Rs + r) * d_m + d] = (f16_t)acc;
 }
 
-// Log-sum-exp merge of partials whose reference maxima are in log2 units.
-__global__ void k_merge_exp2(const float *__restrict__ Xp, const float *__restrict__ ML, float *__restrict__ Xn,
+// Log-sum-exp merge of normalised fp16 partials (reference maxima in log2 units):
+// X = sum_p (w_p l_p) Xhat_p / sum_p (w_p l_p),  w_p = 2^(m_p - M).
+__global__ void k_merge_exp2(const f16_t *__restrict__ Xp, const float *__restrict__ ML, float *__restrict__ Xn,
                              int d_m, int R, int Rs, int parts)
 {
     const int d = blockIdx.x * 256 + threadIdx.x;
@@ -398,9 +440,9 @@ __global__ void k_merge_exp2(const float *__restrict__ Xp, const float *__restri
         const size_t rowi = ((size_t)b * parts + p) * Rs + r;
         const float mp = ML[rowi * 2], lp = ML[rowi * 2 + 1];
         if (lp > 0.f) {
-            const float wgt = exp2f(mp - M);
-            num = fmaf(wgt, Xp[rowi * d_m + d], num);
-            den = fmaf(wgt, lp, den);
+            const float wgt = exp2f(mp - M) * lp;
+            num = fmaf(wgt, (float)Xp[rowi * d_m + d], num);
+            den += wgt;
         }
     }
     Xn[((size_t)b * R + r) * d_m + d] = num / den;
@@ -473,7 +515,7 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
 {
     CoreArgs a;
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
-    a.elq = (const f16_t *)ws.ELQ; a.Xp = ws.Xp; a.ML = ws.ML;
+    a.elq = (const f16_t *)ws.ELQ; a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
 #ifdef EL_CORE_PROF
     a.prof = g_core_prof;
@@ -488,7 +530,7 @@ hipError_t launch_merge_exp2(const el_attn_ctx *, const Problem &p, const Worksp
                              hipStream_t s)
 {
     hipLaunchKernelGGL(k_merge_exp2, dim3((p.d_m + 255) / 256, p.R, p.B), dim3(256), 0, s,
-                       (const float *)ws.Xp, (const float *)ws.ML, ws.Xn, p.d_m, p.R, pl.Rs, pl.parts);
+                       (const f16_t *)ws.Xp, (const float *)ws.ML, ws.Xn, p.d_m, p.R, pl.Rs, pl.parts);
     return hipGetLastError();
 }
 

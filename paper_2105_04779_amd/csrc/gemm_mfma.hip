@@ -38,7 +38,7 @@ struct GemmArgs {
     // physical row of logical row m in batch z:  (m / x) * rB + (m % x) * rJ + z * rI
     int a_rB, a_rJ, a_rI, c_rB, c_rJ, c_rI;
     int a_col_z, bt_row_z, bt_col_z, c_col_z;   // per-batch offsets (elements / rows)
-    // A_MERGE: A points at the split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
+    // A_MERGE: A points at the normalised fp16 split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
     const float *ML;
     int parts, Rs;
 };
@@ -101,7 +101,7 @@ k_gemm_nt(const GemmArgs g)
             wgt[p] = 0.f;
             if (p < g.parts) {
                 const float *ml = g.ML + (((size_t)b * g.parts + p) * g.Rs + r) * 2;
-                if (ml[1] > 0.f) { wgt[p] = exp2f(ml[0] - Mx); den = fmaf(wgt[p], ml[1], den); }
+                if (ml[1] > 0.f) { wgt[p] = exp2f(ml[0] - Mx) * ml[1]; den += wgt[p]; }
             }
         }
         const float inv = 1.0f / den;
@@ -163,12 +163,9 @@ k_gemm_nt(const GemmArgs g)
 #pragma unroll
                     for (int p = 0; p < kMaxParts; ++p) {
                         if (p < g.parts && wgt[p] != 0.f) {
-                            const float *ap = (const float *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + k0 + 8 * q4;
-                            const f4 v0 = *(const f4 *)ap, v1 = *(const f4 *)(ap + 4);
-                            v[0] = fmaf(wgt[p], v0[0], v[0]); v[1] = fmaf(wgt[p], v0[1], v[1]);
-                            v[2] = fmaf(wgt[p], v0[2], v[2]); v[3] = fmaf(wgt[p], v0[3], v[3]);
-                            v[4] = fmaf(wgt[p], v1[0], v[4]); v[5] = fmaf(wgt[p], v1[1], v[5]);
-                            v[6] = fmaf(wgt[p], v1[2], v[6]); v[7] = fmaf(wgt[p], v1[3], v[7]);
+                            const h8 xv = *(const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + k0 + 8 * q4);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = fmaf(wgt[p], (float)xv[e], v[e]);
                         }
                     }
                 }

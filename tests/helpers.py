@@ -52,3 +52,17 @@ def gpu_out(layer, w, H, Q, lens):
     out = layer.decode_step(Hd, Ld, Qd)
     torch.cuda.synchronize()
     return out.float().cpu().numpy()
+
+
+def record(line: str):
+    """Append one line to gpurun_out/parity_errors.txt (kept out of git) and print it."""
+    import os
+    print(line, flush=True)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    d = os.path.join(root, "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "parity_errors.txt"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2105_04779_amd import workloads as wl
-from helpers import TOL, gpu_out, make_layer, oracle_out, rel_err, to_device
+from helpers import TOL, gpu_out, make_layer, oracle_out, record, rel_err, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -30,7 +30,7 @@ def run_case(w, *, lens=None, poison=True, flags=0, splits=0, scale_q=None, elem
     y = gpu_out(layer, w, Hp, Q, L)
     err = rel_err(y, ref)
     bar = tol or TOL[w.dtype]
-    print(f"{w.name}: B={H.shape[0]} mfma={layer.uses_mfma} splits={splits} err={err:.3e} bar={bar:g}", flush=True)
+    record(f"{w.name}: B={H.shape[0]} mfma={layer.uses_mfma} splits={splits} err={err:.3e} bar={bar:g}")
     assert err <= bar, f"{w.name}: err {err:.3e} > {bar:g}"
     layer.close()
     return y
@@ -253,6 +253,6 @@ def test_full_size_sampled(name):
     y = out[sample].float().cpu().numpy()
     ref = oracle_out(w, W, Hs, Qs, Ls)
     err = rel_err(y, ref)
-    print(f"{name}: sampled {sample} mfma={layer.uses_mfma} err={err:.3e}", flush=True)
+    record(f"{name}: sampled {sample} mfma={layer.uses_mfma} err={err:.3e} bar={TOL[w.dtype]:g}")
     assert err <= TOL[w.dtype]
     assert torch.isfinite(out).all()
