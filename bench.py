@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--splits", type=int, default=0, help="key-range splits (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
     ap.add_argument("--same-h", action="store_true", help="reuse one H buffer every step (cache-warm; not the reported protocol)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only run a plain device copy of known size (1 GiB read + 1 GiB written per launch, 10 launches): "
+                         "what FETCH_SIZE / WRITE_SIZE read for it scales the counters of the real run")
     return ap.parse_args()
 
 
@@ -77,6 +80,16 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.pmc_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": src.numel() * 4,
+                          "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
+        return
     w = wl.WORKLOADS[a.workload]
     td = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
 

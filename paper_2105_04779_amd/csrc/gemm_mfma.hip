@@ -302,7 +302,8 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     g.bt_row_z = p.d_k;
     g.c_rB = p.beam; g.c_rJ = 1; g.c_col_z = p.d_k;
     const bool bf = p.dtype == EL_BF16;
-    return launch_gemm<A_MERGE, C_F32, 2, 1, 4, 4>(g, bf, p.heads, s);
+    // one workgroup covers a head's whole d_k = 64 columns, so every partial row is read by one workgroup only
+    return launch_gemm<A_MERGE, C_F32, 4, 1, 4, 4>(g, bf, p.heads, s);
 }
 
 // a7: out = A . W^O + c_out
