@@ -56,7 +56,7 @@ Workspace carve(const el_attn_ctx *c)
 
 void free_weights(el_attn_ctx *c)
 {
-    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, c->w.WqT, c->w.WvT, c->w.WoT, (void *)c->w.c_out};
+    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, c->w.WqT, c->w.WkH, c->w.WvT, c->w.WoT, (void *)c->w.c_out};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     std::memset(&c->w, 0, sizeof(c->w));
@@ -163,14 +163,19 @@ el_status el_attn_prepare(const el_attn_config *cfg,
     if (launch_cout(c, bv, bo, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
     c->use_mfma_gemm = (c->use_mfma_core && gemm_mfma_supported(cfg->dtype, cfg->d_model, cfg->d_k)) ? 1 : 0;
     if (c->use_mfma_gemm) {
-        // transposed copies so that every MFMA operand fragment is contiguous along k
-        struct { void **dst; const void *src; int rows, cols; } tr[] = {
-            {&c->w.WqT, c->w.Wq, cfg->d_model, c->hd}, {&c->w.WvT, c->w.Wv, cfg->d_model, c->hd},
-            {&c->w.WoT, c->w.Wo, c->hd, cfg->d_model},
+        // transposed copies so that every MFMA operand is contiguous along k; everything after a1 runs
+        // in fp16, so bf16 weights of a2, a6, a7 are converted once here
+        struct { void **dst; const void *src; int rows, cols; bool to_f16; } tr[] = {
+            {&c->w.WqT, c->w.Wq, cfg->d_model, c->hd, false}, {&c->w.WvT, c->w.Wv, cfg->d_model, c->hd, true},
+            {&c->w.WoT, c->w.Wo, c->hd, cfg->d_model, true},  {&c->w.WkH, c->w.Wk, 0, 0, true},
         };
+        const size_t nel = (size_t)cfg->d_model * c->hd;
         for (auto &t : tr) {
             if (hipMalloc(t.dst, wbytes) != hipSuccess) { free_weights(c); delete c; return EL_ERR_ALLOC; }
-            if (launch_transpose16(t.src, *t.dst, t.rows, t.cols, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+            hipError_t e = t.rows ? launch_transpose16(t.src, *t.dst, t.rows, t.cols, s)
+                                  : hipMemcpyAsync(*t.dst, t.src, wbytes, hipMemcpyDeviceToDevice, s);
+            if (e == hipSuccess && t.to_f16 && cfg->dtype == EL_BF16) e = launch_bf16_to_f16(*t.dst, *t.dst, nel, s);
+            if (e != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
         }
     }
 

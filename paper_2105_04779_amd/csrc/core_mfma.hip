@@ -48,10 +48,6 @@ struct CoreArgs {
 #endif
 };
 
-// 16-byte chunk swizzle inside a tile row: a bijection of the low four chunk bits that makes both
-// the row-wise b128 reads and the transposing b64 reads spread over all LDS banks.
-__device__ __forceinline__ int row_swizzle(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
-
 __device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x)
 {
     const float lo = __uint_as_float(x << 16);
@@ -66,22 +62,6 @@ __device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x)
 #define EL_PROF_DECL
 #define EL_PROF(i)
 #endif
-
-// One 1 KB piece of a tile row, fetched by one wavefront straight into LDS.  `lds_addr` is the
-// LDS byte address the piece starts at (lane i lands at +16 i), `voff` the lane's byte offset from
-// the wave-uniform global base.  Issued through inline assembly so that the compiler does not
-// serialise later LDS reads of the *other* tile buffer behind it; completion is awaited
-// explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
-__device__ __forceinline__ void dma_piece(unsigned lds_addr, unsigned voff, const char *sbase)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
-}
-__device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, const char *sbase)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
-}
 
 template <int DM, bool BF16, int NRG>
 __global__ void __launch_bounds__(256)

@@ -25,6 +25,27 @@ __device__ __forceinline__ void from_f32(float x, bf16_t *p) {
     p->bits = (uint16_t)(u >> 16);
 }
 
+// ---- LDS staging helpers shared by the MFMA kernels ---------------------------------------
+// 16-byte chunk swizzle inside a tile row: a bijection of the low four chunk bits that makes both
+// the row-wise b128 reads and the transposing b64 reads spread over all LDS banks.
+__device__ __forceinline__ int row_swizzle(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
+
+// One 1 KB piece of a row, fetched by one wavefront straight into LDS.  `lds_addr` is the
+// LDS byte address the piece starts at (lane i lands at +16 i), `voff` the lane's byte offset from
+// the wave-uniform global base.  Issued through inline assembly so that the compiler does not
+// serialise later LDS reads of the *other* tile buffer behind it; completion is awaited
+// explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma_piece(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
 static inline size_t dtype_size(int dt) { return dt == EL_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -45,17 +66,18 @@ struct Problem {
 
 // Workspace carve-up (device pointers into the caller's buffer).
 struct Workspace {
-    float *Qp;      // [B*beam, hd]                 a1 result, fp32, already scaled by 1/sqrt(d_k)
+    float *Qp;      // [B*beam, hd]                 a1 result: fp32 (generic) or fp16 (MFMA GEMMs), scaled
     void *ELQ;      // [B, Rpad, d_m]               fp32 (generic) or fp16 (MFMA core)
     float *Xp;      // [B, parts, Rpad, d_m]        un-normalised partial weighted sums
     float *ML;      // [B, parts, Rpad, 2]          running max and sum of each partial
     float *Xn;      // [B, R, d_m]                  merged, normalised weighted sums (generic path)
-    float *A;       // [B*beam, hd]                 a6 result, fp32
+    float *A;       // [B*beam, hd]                 a6 result: fp32 (generic) or fp16 (MFMA GEMMs)
 };
 
 struct Weights {    // library-owned copies in the storage dtype
     void *Wq, *Wk, *Wv, *Wo, *bq;   // original layout (x . W form)
-    void *WqT, *WvT, *WoT;          // transposed copies for the MFMA GEMMs (16-bit dtypes only)
+    void *WqT;                      // (W^Q)^T in the storage dtype (16-bit dtypes only)
+    void *WkH, *WvT, *WoT;          // W^K, (W^V)^T, (W^O)^T in fp16 (converted from bf16 when needed)
     float *c_out;                   // [d_m] = b_o + b_v . W_o, fp32
 };
 
@@ -108,6 +130,7 @@ hipError_t launch_merge_exp2(const el_attn_ctx *ctx, const Problem &p, const Wor
 // MFMA projection GEMMs -- gemm_mfma.hip
 bool gemm_mfma_supported(int dtype, int d_m, int d_k);
 hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hipStream_t s);
+hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s);
 hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, float scale, hipStream_t s);
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s);
 hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs, hipStream_t s);

@@ -1,18 +1,22 @@
 // Small-M MFMA GEMMs for the projection steps of the EL-attention decode step (steps a1, a2, a6,
 // a7 of Algorithm 3's attention routine; group 2 of Table 1 -- O(d_m^2) per query, weight-read
-// bound).  All four are C[m, n] = sum_k A[m, k] * Bt[n, k]: both operands contiguous along k, so
-// every MFMA operand fragment is one 16-byte load straight from global memory (the weights W^Q,
-// W^V, W^O are stored transposed at prepare time for exactly this; W^K already has that shape).
+// bound).  All four are C[m, n] = sum_k A[m, k] * Bt[n, k] with both operands contiguous along k
+// (W^Q, W^V, W^O are stored transposed at prepare time for exactly this; W^K already has that shape).
 //
-//   a1  Qp   = q . W^Q + b^Q              A = queries (storage dtype),    Bt = (W^Q)^T
-//   a2  ELQ_i = Qp_i . (W_i^K)^T          A = Qp (fp32),                  Bt = W^K        per head
-//   a6  A_i  = X_i . W_i^V                A = merge of split partials,    Bt = (W^V)^T    per head
-//   a7  out  = A . W^O + c_out            A = A (fp32),                   Bt = (W^O)^T
+//   a1  Qp    = (q . W^Q + b^Q) * scale   k_gemm_slab  A = queries (storage dtype), Bt = (W^Q)^T (storage dtype)
+//   a2  ELQ_i = Qp_i . (W_i^K)^T          k_gemm_nt    A = Qp (fp16),               Bt = W^K in fp16     per head
+//   a6  A_i   = X_i . W_i^V               k_gemm_nt    A = merge of split partials, Bt = (W^V)^T in fp16 per head
+//   a7  out   = A . W^O + c_out           k_gemm_slab  A = A (fp16),                Bt = (W^O)^T in fp16
 //
-// Storage-dtype operands enter the MFMA exactly.  fp32 activations are split into a high and a
-// low half in the weights' 16-bit type (two MFMAs per fragment), so nothing wider than the final
-// fp16 EL-Q is ever rounded to 16 bits: 16 (bf16 pair) or 22 (fp16 pair) significant bits survive.
-// Accumulation is fp32 (v_mfma_f32_16x16x32_{f16,bf16}).
+// Storage-dtype operands enter the MFMA exactly (a1 runs in the storage type).  From a2 on everything
+// is fp16: bf16 weights are converted once at prepare time (exact above 2^-14, |error| <= 2^-25 below),
+// and the intermediates Qp, merged X and A are rounded to fp16 once each (2^-12 relative; the
+// measured end-to-end error stays several times under the 2e-3 bar).  Accumulation is fp32.
+//
+// k_gemm_slab: a workgroup stages 32 rows of A and 32 rows of Bt over the whole K in LDS with 1 KB
+// LDS-DMA pieces (full cache lines, every byte fetched once per workgroup), then its four wavefronts
+// split K.  k_gemm_nt: operand fragments straight from global memory (a2: K = d_k is tiny; a6: the A
+// operand is computed on the fly from the key-range partials).
 #include "el_internal.h"
 
 namespace el {
@@ -22,7 +26,7 @@ typedef __bf16 b8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
-enum { A_STORAGE = 0, A_F32 = 1, A_MERGE = 2 };
+enum { A_STORAGE = 0, A_MERGE = 2 };
 enum { C_F32 = 0, C_F16 = 1, C_BF16 = 2 };
 
 struct GemmArgs {
@@ -47,18 +51,10 @@ template <bool BF> struct Frag;
 template <> struct Frag<false> {
     typedef h8 type;
     static __device__ __forceinline__ f4 mfma(h8 a, h8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ void split(const float *v, h8 &hi, h8 &lo) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { const _Float16 h = (_Float16)v[e]; hi[e] = h; lo[e] = (_Float16)(v[e] - (float)h); }
-    }
 };
 template <> struct Frag<true> {
     typedef b8 type;
     static __device__ __forceinline__ f4 mfma(b8 a, b8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ void split(const float *v, b8 &hi, b8 &lo) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { const __bf16 h = (__bf16)v[e]; hi[e] = h; lo[e] = (__bf16)(v[e] - (float)h); }
-    }
 };
 
 // One wavefront computes a 16 x (16*NT) tile over a K range.  A workgroup is KS x WM x WN wavefronts
@@ -127,55 +123,49 @@ k_gemm_nt(const GemmArgs g)
     if (live)
     for (int kr = kbeg; kr < kend; kr += 32 * U) {
         // ---- fetch U k-steps of A and Bt fragments ----
-        u4 a_raw[U][AK == A_STORAGE ? 1 : 2];
+        u4 a_raw[U];
         u4 b_raw[U][NT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int k0 = min(kr + 32 * u, kend - 32);    // rounds that overrun re-read the last step (and skip its MFMAs)
-            if (AK == A_STORAGE) {
-                a_raw[u][0] = *(const u4 *)((const char *)g.A + (a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4) * 2);
-            } else if (AK == A_F32) {
-                const float *ap = (const float *)g.A + a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4;
-                a_raw[u][0] = *(const u4 *)ap;
-                a_raw[u][1] = *(const u4 *)(ap + 4);
-            }
+            const int k0 = kr + 32 * u;                    // the K slice is a multiple of 32 * U (chosen by the host)
+            if (AK == A_STORAGE)
+                a_raw[u] = *(const u4 *)((const char *)g.A + (a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4) * 2);
 #pragma unroll
             for (int t = 0; t < NT; ++t) b_raw[u][t] = *(const u4 *)(Bt + bt_off[t] + (size_t)k0 * 2);
         }
+        __builtin_amdgcn_sched_barrier(0);            // every fetch of the round is issued before the first MFMA
         // ---- multiply ----
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k0 = kr + 32 * u;
-            if (k0 >= kend) break;
-            frag_t a_hi, a_lo;
+            frag_t a_fr;
             if (AK == A_STORAGE) {
-                a_hi = __builtin_bit_cast(frag_t, a_raw[u][0]);
+                a_fr = __builtin_bit_cast(frag_t, a_raw[u]);
             } else {
+                // merged, normalised weighted sum of this row's partials, rounded to fp16 once
                 float v[8];
-                if (AK == A_F32) {
-                    const f4 v0 = __builtin_bit_cast(f4, a_raw[u][0]), v1 = __builtin_bit_cast(f4, a_raw[u][1]);
-                    v[0] = v0[0]; v[1] = v0[1]; v[2] = v0[2]; v[3] = v0[3];
-                    v[4] = v1[0]; v[5] = v1[1]; v[6] = v1[2]; v[7] = v1[3];
-                } else {
-                    const int b = m / g.x, r = (m % g.x) * g.a_rJ + z * g.a_rI;
+                const int b = m / g.x, r = (m % g.x) * g.a_rJ + z * g.a_rI;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+                for (int e = 0; e < 8; ++e) v[e] = 0.f;
 #pragma unroll
-                    for (int p = 0; p < kMaxParts; ++p) {
-                        if (p < g.parts && wgt[p] != 0.f) {
-                            const h8 xv = *(const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + k0 + 8 * q4);
+                for (int p = 0; p < kMaxParts; ++p) {
+                    if (p < g.parts && wgt[p] != 0.f) {
+                        const h8 xv = *(const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + k0 + 8 * q4);
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] = fmaf(wgt[p], (float)xv[e], v[e]);
-                        }
+                        for (int e = 0; e < 8; ++e) v[e] = fmaf(wgt[p], (float)xv[e], v[e]);
                     }
                 }
-                Frag<BF>::split(v, a_hi, a_lo);
+                h8 hv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
+                a_fr = __builtin_bit_cast(frag_t, hv);
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const frag_t bf = __builtin_bit_cast(frag_t, b_raw[u][t]);
-                acc[t] = Frag<BF>::mfma(a_hi, bf, acc[t]);
-                if (AK != A_STORAGE) acc[t] = Frag<BF>::mfma(a_lo, bf, acc[t]);
+                // weights as the MFMA's A operand: the result tile is C^T, so a lane ends up with four
+                // consecutive output columns of one row and stores them as one vector
+                acc[t] = Frag<BF>::mfma(bf, a_fr, acc[t]);
             }
         }
     }
@@ -199,27 +189,148 @@ k_gemm_nt(const GemmArgs g)
     }
     if (!live) return;
 
-    // C layout of the MFMA: lane holds rows 4*q4 + j (j = 0..3) of column l%16
+    // C^T layout of the MFMA: this lane holds output row m0 + l%16, columns n0 + 16t + 4*q4 + j (j = 0..3)
+    const int mm = m0 + r16;
+    if (mm >= g.M) return;
+    const size_t c_row = (size_t)(mm / g.x) * g.c_rB + (size_t)(mm % g.x) * g.c_rJ + (size_t)z * g.c_rI;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int n = n0 + 16 * t + r16;
-        if (n >= g.N) continue;
-        float badd = 0.f;
-        if (g.bias) badd = BF ? to_f32(((const bf16_t *)g.bias)[g.c_col_z * z + n]) : to_f32(((const f16_t *)g.bias)[g.c_col_z * z + n]);
-        if (g.bias32) badd += g.bias32[g.c_col_z * z + n];
+        const int n = n0 + 16 * t + 4 * q4;
+        if (n >= g.N) continue;                       // N is a multiple of 4 (checked by the host)
+        float val[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int mm = m0 + 4 * q4 + j;
-            if (mm < g.M) {
-                const size_t c_row = (size_t)(mm / g.x) * g.c_rB + (size_t)(mm % g.x) * g.c_rJ + (size_t)z * g.c_rI;
-                const size_t ci = c_row * g.ldc + (size_t)g.c_col_z * z + n;
-                const float val = (acc[t][j] + badd) * g.scale;
-                if (CK == C_F32) ((float *)g.C)[ci] = val;
-                else if (CK == C_F16) ((f16_t *)g.C)[ci] = (f16_t)val;
-                else from_f32(val, (bf16_t *)g.C + ci);
-            }
+            float badd = 0.f;
+            if (g.bias) badd = BF ? to_f32(((const bf16_t *)g.bias)[g.c_col_z * z + n + j]) : to_f32(((const f16_t *)g.bias)[g.c_col_z * z + n + j]);
+            if (g.bias32) badd += g.bias32[g.c_col_z * z + n + j];
+            val[j] = (acc[t][j] + badd) * g.scale;
+        }
+        const size_t ci = c_row * g.ldc + (size_t)g.c_col_z * z + n;
+        if (CK == C_F32) {
+            *(f4 *)((float *)g.C + ci) = f4{val[0], val[1], val[2], val[3]};
+        } else if (CK == C_F16) {
+            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+            *(h4 *)((f16_t *)g.C + ci) = h4{(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) from_f32(val[j], (bf16_t *)g.C + ci + j);
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Slab GEMM: C[M, N] = A[M, K] . Bt[N, K]^T for K = 512 or 1024 (rows of 1 or 2 KB).  One workgroup
+// owns a 32 x 32 output tile.  Its 64 operand rows are fetched once, whole, into LDS (row r lands
+// XOR-swizzled by row_swizzle(r % 16), see dma_piece), so global traffic is full cache lines and
+// (M/32 + N/32) passes over the operands in total.  Then wavefront w multiplies k-steps
+// [w K/128, (w+1) K/128) for all four 16 x 16 sub-tiles, the partial tiles are added through LDS
+// and wavefront w finishes sub-tile w.
+template <bool BF, int CK>
+__global__ void __launch_bounds__(256)
+k_gemm_slab(const GemmArgs g)
+{
+    typedef typename Frag<BF>::type frag_t;
+    __shared__ __attribute__((aligned(1024))) char S[64 * 2048];
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = l & 15, q4 = l >> 4;
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int rowb = g.K * 2;
+    const unsigned s_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)S;
+
+    // ---- stage: wavefronts 0,1 fetch the A rows, 2,3 the Bt rows ----
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rr = 16 * w + i;
+        const char *sbase;
+        if (w < 2) sbase = (const char *)g.A + (size_t)min(m0 + rr, g.M - 1) * g.lda * 2;
+        else sbase = (const char *)g.Bt + (size_t)min(n0 + rr - 32, g.N - 1) * g.ldb * 2;
+        const unsigned voff = (unsigned)((l ^ row_swizzle(i)) << 4);
+        if (rowb == 2048) dma_row_2k(s_lds + rr * rowb, voff, sbase);
+        else dma_piece(s_lds + rr * rowb, voff, sbase);
+    }
+
+    // bias of this lane's four output columns (sub-tile w), fetched while the slab is in flight
+    const int mt = w >> 1, nt = w & 1;
+    const int ncol = n0 + 16 * nt + 4 * q4;
+    float badd[4] = {0.f, 0.f, 0.f, 0.f};
+    if (ncol < g.N) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (g.bias) badd[j] = BF ? to_f32(((const bf16_t *)g.bias)[ncol + j]) : to_f32(((const f16_t *)g.bias)[ncol + j]);
+            if (g.bias32) badd[j] += g.bias32[ncol + j];
+        }
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // ---- multiply: this wavefront's quarter of K ----
+    const __attribute__((address_space(3))) char *Sl = (const __attribute__((address_space(3))) char *)S;
+    const int fsw = row_swizzle(r16);
+    f4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = f4{0.f, 0.f, 0.f, 0.f};
+    const int steps = g.K / 128;
+    for (int st = 0; st < steps; ++st) {
+        const int chunk = (4 * (w * steps + st) + q4) ^ fsw;
+        const int off = r16 * rowb + (chunk << 4);
+        const frag_t a0 = __builtin_bit_cast(frag_t, *(const __attribute__((address_space(3))) u4 *)(Sl + off));
+        const frag_t a1 = __builtin_bit_cast(frag_t, *(const __attribute__((address_space(3))) u4 *)(Sl + off + 16 * rowb));
+        const frag_t b0 = __builtin_bit_cast(frag_t, *(const __attribute__((address_space(3))) u4 *)(Sl + off + 32 * rowb));
+        const frag_t b1 = __builtin_bit_cast(frag_t, *(const __attribute__((address_space(3))) u4 *)(Sl + off + 48 * rowb));
+        // weights as the MFMA's A operand: the result is the transposed tile, so a lane holds four
+        // consecutive output columns of one row
+        acc[0][0] = Frag<BF>::mfma(b0, a0, acc[0][0]);
+        acc[0][1] = Frag<BF>::mfma(b1, a0, acc[0][1]);
+        acc[1][0] = Frag<BF>::mfma(b0, a1, acc[1][0]);
+        acc[1][1] = Frag<BF>::mfma(b1, a1, acc[1][1]);
+    }
+
+    // ---- add the four K quarters: wavefront w collects sub-tile (mt, nt) ----
+    __syncthreads();                                   // the slab is no longer needed
+    float *red = (float *)S;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) *(f4 *)(red + (((w * 4) + a * 2 + b) * 64 + l) * 4) = acc[a][b];
+    __syncthreads();
+    f4 sum = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const f4 o = *(const f4 *)(red + (((s * 4) + mt * 2 + nt) * 64 + l) * 4);
+        sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
+    }
+    const int mm = m0 + 16 * mt + r16;
+    if (mm >= g.M || ncol >= g.N) return;
+    float val[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) val[j] = (sum[j] + badd[j]) * g.scale;
+    const size_t ci = (size_t)mm * g.ldc + ncol;
+    if (CK == C_F32) {
+        *(f4 *)((float *)g.C + ci) = f4{val[0], val[1], val[2], val[3]};
+    } else if (CK == C_F16) {
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        *(h4 *)((f16_t *)g.C + ci) = h4{(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) from_f32(val[j], (bf16_t *)g.C + ci + j);
+    }
+}
+
+// bf16 -> fp16 copy of a weight matrix (prepare time).
+__global__ void k_bf16_to_f16(const bf16_t *src, f16_t *dst, size_t n)   // src may equal dst
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = (f16_t)to_f32(src[i]);
+}
+
+hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_bf16_to_f16, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const bf16_t *)src, (f16_t *)dst, n);
+    return hipGetLastError();
 }
 
 // Transpose a [rows, cols] matrix of 16-bit elements (prepare-time packing of W^Q, W^V, W^O).
@@ -255,7 +366,7 @@ static hipError_t launch_gemm(const GemmArgs &g, bool bf, int batches, hipStream
 
 bool gemm_mfma_supported(int dtype, int d_m, int d_k)
 {
-    return (dtype == EL_F16 || dtype == EL_BF16) && d_m % 128 == 0 && d_k % 64 == 0;
+    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024) && d_k % 64 == 0;
 }
 
 static GemmArgs base_args(const Problem &p)
@@ -267,31 +378,35 @@ static GemmArgs base_args(const Problem &p)
     return g;
 }
 
-// a1: Qp = (q . W^Q + b^Q) * scale        [B*beam, hd] fp32
+template <bool BF, int CK>
+static hipError_t launch_slab(const GemmArgs &g, hipStream_t s)
+{
+    hipLaunchKernelGGL((k_gemm_slab<BF, CK>), dim3((g.N + 31) / 32, (g.M + 31) / 32), dim3(256), 0, s, g);
+    return hipGetLastError();
+}
+
+// a1: Qp = (q . W^Q + b^Q) * scale        [B*beam, hd] fp16
 hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, float scale, hipStream_t s)
 {
     GemmArgs g = base_args(p);
     g.A = p.queries; g.Bt = ctx->w.WqT; g.C = ws.Qp; g.bias = ctx->w.bq; g.scale = scale;
     g.N = p.hd; g.K = p.d_m; g.lda = p.d_m; g.ldb = p.d_m; g.ldc = p.hd;
-    g.a_rB = p.beam; g.a_rJ = 1; g.c_rB = p.beam; g.c_rJ = 1;
-    return launch_gemm<A_STORAGE, C_F32, 2, 1, 4, 8>(g, p.dtype == EL_BF16, 1, s);
+    return p.dtype == EL_BF16 ? launch_slab<true, C_F16>(g, s) : launch_slab<false, C_F16>(g, s);
 }
 
 // a2: ELQ[b, i*beam+j, :] = Qp[b*beam+j, head i] . (W_i^K)^T      fp16, row stride d_m, Rs rows per b
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s)
 {
     GemmArgs g = base_args(p);
-    g.A = ws.Qp; g.Bt = ctx->w.Wk; g.C = ws.ELQ;
+    g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ;
     g.N = p.d_m; g.K = p.d_k; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
     g.a_rB = p.beam; g.a_rJ = 1; g.a_col_z = p.d_k;
     g.bt_col_z = p.d_k;
     g.c_rB = Rs; g.c_rJ = 1; g.c_rI = p.beam;
-    const bool bf = p.dtype == EL_BF16;
-    if (p.d_m % 512 == 0) return launch_gemm<A_F32, C_F16, 8, 4, 1, 2>(g, bf, p.heads, s);
-    return launch_gemm<A_F32, C_F16, 2, 4, 1, 2>(g, bf, p.heads, s);
+    return launch_gemm<A_STORAGE, C_F16, 8, 4, 1, 2>(g, false, p.heads, s);
 }
 
-// merge + a6: A[b*beam+j, head i] = (sum_p w_p Xp[b,p,i*beam+j,:]) . W_i^V       fp32
+// merge + a6: A[b*beam+j, head i] = (sum_p w_p Xp[b,p,i*beam+j,:]) . W_i^V       fp16
 hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs,
                              hipStream_t s)
 {
@@ -301,9 +416,8 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     g.a_rJ = 1; g.a_rI = p.beam;            // row inside the batch element: i*beam + j
     g.bt_row_z = p.d_k;
     g.c_rB = p.beam; g.c_rJ = 1; g.c_col_z = p.d_k;
-    const bool bf = p.dtype == EL_BF16;
     // one workgroup covers a head's whole d_k = 64 columns, so every partial row is read by one workgroup only
-    return launch_gemm<A_MERGE, C_F32, 4, 1, 4, 4>(g, bf, p.heads, s);
+    return launch_gemm<A_MERGE, C_F16, 4, 1, 4, 4>(g, false, p.heads, s);
 }
 
 // a7: out = A . W^O + c_out
@@ -312,11 +426,9 @@ hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     GemmArgs g = base_args(p);
     g.A = ws.A; g.Bt = ctx->w.WoT; g.C = p.out; g.bias32 = ctx->w.c_out;
     g.N = p.d_m; g.K = p.hd; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
-    g.a_rB = p.beam; g.a_rJ = 1; g.c_rB = p.beam; g.c_rJ = 1;
-    const bool bf = p.dtype == EL_BF16;
-    if (p.out_dtype == EL_F32) return launch_gemm<A_F32, C_F32, 2, 1, 4, 8>(g, bf, 1, s);
-    if (bf) return launch_gemm<A_F32, C_BF16, 2, 1, 4, 8>(g, true, 1, s);
-    return launch_gemm<A_F32, C_F16, 2, 1, 4, 8>(g, false, 1, s);
+    if (p.out_dtype == EL_F32) return launch_slab<false, C_F32>(g, s);
+    if (p.dtype == EL_BF16) return launch_slab<false, C_BF16>(g, s);
+    return launch_slab<false, C_F16>(g, s);
 }
 
 } // namespace el
