@@ -20,6 +20,7 @@
 // for the whole range.  With fewer than 64 rows the spare wavefronts take alternate tiles and
 // produce partial results of their own; all partials (key-range splits and wavefront parities)
 // are combined afterwards by the log-sum-exp merge.
+#include <cstdlib>
 #include "el_internal.h"
 
 namespace el {
@@ -35,18 +36,6 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 constexpr int kTileRows = 32;
 constexpr float kRescaleStep = 10.0f; // log2 units: probabilities stay below 2^10
 
-struct CoreArgs {
-    const void *H;
-    int64_t h_stride;        // elements between batch elements
-    const int32_t *lengths;
-    const f16_t *elq;        // [B, Rs, DM] fp16, scaled by log2(e)/sqrt(d_k), pad rows zero
-    f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
-    float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
-    int n, B, R, Rs, S, nblocks;
-#ifdef EL_CORE_PROF
-    unsigned long long *prof;   // per-phase cycle totals of workgroup 0, wave 0 (debug builds only)
-#endif
-};
 
 __device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x)
 {
@@ -439,6 +428,19 @@ bool core_mfma_supported(int dtype, int d_m)
     return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024);
 }
 
+// Two attention-core kernels exist.  The column-split kernel (core_ds.hip) reads every tile byte from
+// LDS only twice and has no per-wavefront partials, which wins when few rows share one H (greedy
+// decoding, per-beam histories: 16 or 32 rows).  With 64 rows per H the row-split kernel below, with
+// its larger tiles and fewer synchronisation points per byte, is still the faster one as measured.
+// ELATTN_CORE=rows|cols forces one of them (tuning only).
+static bool row_split_core(int R)
+{
+    static const char *force = getenv("ELATTN_CORE");
+    if (force && force[0] == 'r') return true;
+    if (force && force[0] == 'c') return false;
+    return R > 32;
+}
+
 CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override)
 {
     CorePlan pl;
@@ -448,7 +450,7 @@ CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override)
     if (nrg_override > 0 && nrg_override < pl.nrg) pl.nrg = nrg_override;
     pl.nblocks = (p.R + 16 * pl.nrg - 1) / (16 * pl.nrg);
     pl.Rs = pl.nblocks * 16 * pl.nrg;
-    const int ts = 4 / pl.nrg;
+    const int ts = row_split_core(p.R) ? 4 / pl.nrg : 1;   // the column-split kernel has no per-wavefront partials
     const int max_s = kMaxParts / ts;
     int S = splits_override;
     if (S <= 0) {
@@ -501,6 +503,7 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.prof = g_core_prof;
 #endif
     const bool bf = p.dtype == EL_BF16;
+    if (!row_split_core(p.R)) return launch_core_ds(a, p.d_m, bf, pl.nrg, s);
     if (p.d_m == 1024) return bf ? launch_core_t<1024, true>(a, pl.nrg, s) : launch_core_t<1024, false>(a, pl.nrg, s);
     if (p.d_m == 512) return bf ? launch_core_t<512, true>(a, pl.nrg, s) : launch_core_t<512, false>(a, pl.nrg, s);
     return hipErrorInvalidValue;

@@ -113,7 +113,20 @@ hipError_t launch_merge_generic(const el_attn_ctx *ctx, const Problem &p, const 
 hipError_t launch_vproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
 hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
 
-// MFMA attention core -- core_mfma.hip
+// MFMA attention core -- core_ds.hip (column-split kernel), core_mfma.hip (planning, launch, helpers)
+struct CoreArgs {
+    const void *H;
+    int64_t h_stride;        // elements between batch elements
+    const int32_t *lengths;
+    const f16_t *elq;        // [B, Rs, DM] fp16, scaled by log2(e)/sqrt(d_k), pad rows zero
+    f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
+    float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
+    int n, B, R, Rs, S, nblocks;
+#ifdef EL_CORE_PROF
+    unsigned long long *prof;   // per-phase cycle totals of workgroup 0, wave 0 (debug builds only)
+#endif
+};
+hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s);
 struct CorePlan {
     int nrg;      // 16-row groups per workgroup (1, 2 or 4)
     int nblocks;  // row blocks (workgroups sharing one H range)

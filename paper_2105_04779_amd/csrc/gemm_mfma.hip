@@ -5,7 +5,7 @@
 //
 //   a1  Qp    = (q . W^Q + b^Q) * scale   k_gemm_slab  A = queries (storage dtype), Bt = (W^Q)^T (storage dtype)
 //   a2  ELQ_i = Qp_i . (W_i^K)^T          k_gemm_nt    A = Qp (fp16),               Bt = W^K in fp16     per head
-//   a6  A_i   = X_i . W_i^V               k_gemm_nt    A = merge of split partials, Bt = (W^V)^T in fp16 per head
+//   a6  A_i   = X_i . W_i^V               k_vproj_slab A = merge of split partials, Bt = (W^V)^T in fp16 per head
 //   a7  out   = A . W^O + c_out           k_gemm_slab  A = A (fp16),                Bt = (W^O)^T in fp16
 //
 // Storage-dtype operands enter the MFMA exactly (a1 runs in the storage type).  From a2 on everything
@@ -15,8 +15,8 @@
 //
 // k_gemm_slab: a workgroup stages 32 rows of A and 32 rows of Bt over the whole K in LDS with 1 KB
 // LDS-DMA pieces (full cache lines, every byte fetched once per workgroup), then its four wavefronts
-// split K.  k_gemm_nt: operand fragments straight from global memory (a2: K = d_k is tiny; a6: the A
-// operand is computed on the fly from the key-range partials).
+// split K.  k_vproj_slab: the same with the A rows built in LDS from the key-range partials.
+// k_gemm_nt: operand fragments straight from global memory (a2: K = d_k is tiny).
 #include "el_internal.h"
 
 namespace el {
@@ -26,7 +26,7 @@ typedef __bf16 b8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
-enum { A_STORAGE = 0, A_MERGE = 2 };
+enum { A_STORAGE = 0 };
 enum { C_F32 = 0, C_F16 = 1, C_BF16 = 2 };
 
 struct GemmArgs {
@@ -42,7 +42,7 @@ struct GemmArgs {
     // physical row of logical row m in batch z:  (m / x) * rB + (m % x) * rJ + z * rI
     int a_rB, a_rJ, a_rI, c_rB, c_rJ, c_rI;
     int a_col_z, bt_row_z, bt_col_z, c_col_z;   // per-batch offsets (elements / rows)
-    // A_MERGE: A points at the normalised fp16 split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
+    // k_vproj_slab: A points at the normalised fp16 split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
     const float *ML;
     int parts, Rs;
 };
@@ -82,29 +82,6 @@ k_gemm_nt(const GemmArgs g)
     const int m = min(m0 + r16, g.M - 1);
     const size_t a_row = (size_t)(m / g.x) * g.a_rB + (size_t)(m % g.x) * g.a_rJ + (size_t)z * g.a_rI;
 
-    float wgt[kMaxParts];
-    if (AK == A_MERGE) {
-        // log-sum-exp weights of this row's key-range partials (reference maxima in log2 units)
-        const int b = m / g.x, r = (m % g.x) * g.a_rJ + z * g.a_rI;
-        float Mx = -INFINITY;
-        for (int p = 0; p < g.parts; ++p) {
-            const float *ml = g.ML + (((size_t)b * g.parts + p) * g.Rs + r) * 2;
-            if (ml[1] > 0.f) Mx = fmaxf(Mx, ml[0]);
-        }
-        float den = 0.f;
-#pragma unroll
-        for (int p = 0; p < kMaxParts; ++p) {
-            wgt[p] = 0.f;
-            if (p < g.parts) {
-                const float *ml = g.ML + (((size_t)b * g.parts + p) * g.Rs + r) * 2;
-                if (ml[1] > 0.f) { wgt[p] = exp2f(ml[0] - Mx) * ml[1]; den += wgt[p]; }
-            }
-        }
-        const float inv = 1.0f / den;
-#pragma unroll
-        for (int p = 0; p < kMaxParts; ++p) wgt[p] *= inv;
-    }
-
     const char *Bt = (const char *)g.Bt;
     size_t bt_off[NT];
 #pragma unroll
@@ -128,8 +105,7 @@ k_gemm_nt(const GemmArgs g)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k0 = kr + 32 * u;                    // the K slice is a multiple of 32 * U (chosen by the host)
-            if (AK == A_STORAGE)
-                a_raw[u] = *(const u4 *)((const char *)g.A + (a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4) * 2);
+            a_raw[u] = *(const u4 *)((const char *)g.A + (a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4) * 2);
 #pragma unroll
             for (int t = 0; t < NT; ++t) b_raw[u][t] = *(const u4 *)(Bt + bt_off[t] + (size_t)k0 * 2);
         }
@@ -137,29 +113,7 @@ k_gemm_nt(const GemmArgs g)
         // ---- multiply ----
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int k0 = kr + 32 * u;
-            frag_t a_fr;
-            if (AK == A_STORAGE) {
-                a_fr = __builtin_bit_cast(frag_t, a_raw[u]);
-            } else {
-                // merged, normalised weighted sum of this row's partials, rounded to fp16 once
-                float v[8];
-                const int b = m / g.x, r = (m % g.x) * g.a_rJ + z * g.a_rI;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = 0.f;
-#pragma unroll
-                for (int p = 0; p < kMaxParts; ++p) {
-                    if (p < g.parts && wgt[p] != 0.f) {
-                        const h8 xv = *(const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + k0 + 8 * q4);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = fmaf(wgt[p], (float)xv[e], v[e]);
-                    }
-                }
-                h8 hv;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
-                a_fr = __builtin_bit_cast(frag_t, hv);
-            }
+            const frag_t a_fr = __builtin_bit_cast(frag_t, a_raw[u]);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const frag_t bf = __builtin_bit_cast(frag_t, b_raw[u][t]);
@@ -320,6 +274,154 @@ k_gemm_slab(const GemmArgs g)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Merge of the key-range partials fused with a6 (A_i = X_i . W_i^V, Eq. 5 / Eq. 8), one workgroup
+// per (16 rows, head).  The head's 64 rows of (W^V)^T are fetched whole into LDS by LDS-DMA while
+// the workgroup builds its 16 merged rows there: each wavefront reads the partials of 4 rows
+// (full-row, coalesced), combines them with the log-sum-exp weights
+//     X = sum_p (w_p l_p) Xhat_p / sum_p (w_p l_p),  w_p = 2^(m_p - M),
+// and stores the row in fp16, XOR-swizzled like the weights.  Then the four wavefronts split K,
+// add their 16 x 64 partial tiles through LDS, and wavefront w finishes columns [16w, 16w+16).
+template <int DM>
+__global__ void __launch_bounds__(256)
+k_vproj_slab(const GemmArgs g)
+{
+    constexpr int ROWB = DM * 2;
+    constexpr int A_BYTES = 16 * ROWB, B_BYTES = 64 * ROWB;
+    __shared__ __attribute__((aligned(1024))) char S[A_BYTES + B_BYTES];
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = l & 15, q4 = l >> 4;
+    const int m0 = blockIdx.x * 16, head = blockIdx.y;
+    const unsigned s_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)S;
+
+    // ---- weights of this head: rows 16w..16w+15 of its 64, straight into LDS ----
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rr = 16 * w + i;
+        const char *sbase = (const char *)g.Bt + (size_t)(head * 64 + rr) * g.ldb * 2;
+        const unsigned voff = (unsigned)((l ^ row_swizzle(i)) << 4);
+        if (ROWB == 2048) dma_row_2k(s_lds + A_BYTES + rr * ROWB, voff, sbase);
+        else dma_piece(s_lds + A_BYTES + rr * ROWB, voff, sbase);
+    }
+
+    // ---- merged activation rows 4w..4w+3 ----
+    // Step 1: the log-sum-exp weights of the four rows, one (row, part) pair per lane so that all
+    // statistics are fetched in a single round trip; lane 16*row + part keeps the normalised weight.
+    float wgt_lane;
+    {
+        const int ii = l >> 4, p = l & 15;
+        const int m = min(m0 + 4 * w + ii, g.M - 1);
+        const int b = m / g.x, r = head * g.x + (m % g.x);
+        float mp = -INFINITY, lp = 0.f;
+        if (p < g.parts) {
+            const float *ml = g.ML + (((size_t)b * g.parts + p) * g.Rs + r) * 2;
+            lp = ml[1];
+            if (lp > 0.f) mp = ml[0];
+        }
+        float Mx = mp;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) Mx = fmaxf(Mx, __shfl_xor(Mx, o, 64));
+        float wp = lp > 0.f ? exp2f(mp - Mx) * lp : 0.f;
+        float den = wp;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) den += __shfl_xor(den, o, 64);
+        wgt_lane = den > 0.f ? wp / den : 0.f;
+    }
+    // Step 2: the rows themselves, two in flight at a time (each row: all parts, both halves).
+    {
+        constexpr int HF = ROWB / 1024;
+        auto row_src = [&](int ii, int p, int hf) {
+            const int m = min(m0 + 4 * w + ii, g.M - 1);
+            const int b = m / g.x, r = head * g.x + (m % g.x);
+            return (const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + hf * 512 + 8 * l);
+        };
+        h8 xv[2][HF][4];                               // up to four parts per pass
+        for (int p0 = 0; p0 < g.parts; p0 += 4) {
+            auto load_row = [&](int ii, h8 (*dst)[4]) {
+#pragma unroll
+                for (int hf = 0; hf < HF; ++hf)
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp)
+                        if (p0 + pp < g.parts) dst[hf][pp] = *row_src(ii, p0 + pp, hf);
+            };
+            load_row(0, xv[0]);
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                if (ii + 1 < 4) load_row(ii + 1, xv[(ii + 1) & 1]);
+                const int ar = 4 * w + ii;
+#pragma unroll
+                for (int hf = 0; hf < HF; ++hf) {
+                    float v[8];
+                    char *dst = S + ar * ROWB + (((hf * 64 + l) ^ row_swizzle(ar)) << 4);
+                    if (p0 == 0) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = 0.f;
+                    } else {                               // more than four parts: accumulate onto the fp16 row
+                        const h8 prev = *(const h8 *)dst;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (float)prev[e];
+                    }
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) {
+                        if (p0 + pp < g.parts) {
+                            const float wp = __shfl(wgt_lane, 16 * ii + p0 + pp, 64);
+                            if (wp != 0.f) {                   // an empty part's row was never written
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) v[e] = fmaf(wp, (float)xv[ii & 1][hf][pp][e], v[e]);
+                            }
+                        }
+                    }
+                    h8 hv;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
+                    *(h8 *)dst = hv;
+                }
+            }
+        }
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // ---- multiply: this wavefront's quarter of K ----
+    const __attribute__((address_space(3))) char *Sl = (const __attribute__((address_space(3))) char *)S;
+    const int fsw = row_swizzle(r16);
+    f4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
+    constexpr int STEPS = DM / 128;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const int chunk = (4 * (w * STEPS + st) + q4) ^ fsw;
+        const int off = r16 * ROWB + (chunk << 4);
+        const h8 a0 = *(const __attribute__((address_space(3))) h8 *)(Sl + off);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const h8 bt = *(const __attribute__((address_space(3))) h8 *)(Sl + A_BYTES + 16 * t * ROWB + off);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bt, a0, acc[t], 0, 0, 0);   // transposed tile: lane = row, 4 columns
+        }
+    }
+
+    // ---- add the four K quarters; wavefront w finishes column block w ----
+    __syncthreads();
+    float *red = (float *)S;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) *(f4 *)(red + ((w * 4 + t) * 64 + l) * 4) = acc[t];
+    __syncthreads();
+    f4 sum = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const f4 o = *(const f4 *)(red + ((s * 4 + w) * 64 + l) * 4);
+        sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
+    }
+    const int mm = m0 + r16;
+    if (mm >= g.M) return;
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    *(h4 *)((f16_t *)g.C + (size_t)mm * g.ldc + head * 64 + 16 * w + 4 * q4) =
+        h4{(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
+}
+
 // bf16 -> fp16 copy of a weight matrix (prepare time).
 __global__ void k_bf16_to_f16(const bf16_t *src, f16_t *dst, size_t n)   // src may equal dst
 {
@@ -366,7 +468,7 @@ static hipError_t launch_gemm(const GemmArgs &g, bool bf, int batches, hipStream
 
 bool gemm_mfma_supported(int dtype, int d_m, int d_k)
 {
-    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024) && d_k % 64 == 0;
+    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024) && d_k == 64;
 }
 
 static GemmArgs base_args(const Problem &p)
@@ -406,18 +508,17 @@ hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Works
     return launch_gemm<A_STORAGE, C_F16, 8, 4, 1, 2>(g, false, p.heads, s);
 }
 
-// merge + a6: A[b*beam+j, head i] = (sum_p w_p Xp[b,p,i*beam+j,:]) . W_i^V       fp16
+// merge + a6: A[b*beam+j, head i] = (sum_p w_p Xp[b,p,i*beam+j,:]) . W_i^V       fp16   (d_k = 64)
 hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs,
                              hipStream_t s)
 {
     GemmArgs g = base_args(p);
     g.A = ws.Xp; g.Bt = ctx->w.WvT; g.C = ws.A; g.ML = ws.ML; g.parts = parts; g.Rs = Rs;
     g.N = p.d_k; g.K = p.d_m; g.lda = p.d_m; g.ldb = p.d_m; g.ldc = p.hd;
-    g.a_rJ = 1; g.a_rI = p.beam;            // row inside the batch element: i*beam + j
-    g.bt_row_z = p.d_k;
-    g.c_rB = p.beam; g.c_rJ = 1; g.c_col_z = p.d_k;
-    // one workgroup covers a head's whole d_k = 64 columns, so every partial row is read by one workgroup only
-    return launch_gemm<A_MERGE, C_F16, 4, 1, 4, 4>(g, false, p.heads, s);
+    const dim3 grid((g.M + 15) / 16, p.heads), block(256);
+    if (p.d_m == 1024) hipLaunchKernelGGL((k_vproj_slab<1024>), grid, block, 0, s, g);
+    else hipLaunchKernelGGL((k_vproj_slab<512>), grid, block, 0, s, g);
+    return hipGetLastError();
 }
 
 // a7: out = A . W^O + c_out
