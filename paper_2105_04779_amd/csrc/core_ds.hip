@@ -62,6 +62,15 @@ __device__ __forceinline__ unsigned bf16x2_to_f16x2_ds(unsigned x)
 __device__ __forceinline__ float quad_xor1(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true)); }
 __device__ __forceinline__ float quad_xor2(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true)); }
 
+// eight bf16 values held in the bits of an fp16 fragment -> the same values in fp16
+__device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
+{
+    u4 x = __builtin_bit_cast(u4, v);
+    x.x = bf16x2_to_f16x2_ds(x.x); x.y = bf16x2_to_f16x2_ds(x.y);
+    x.z = bf16x2_to_f16x2_ds(x.z); x.w = bf16x2_to_f16x2_ds(x.w);
+    return __builtin_bit_cast(h8, x);
+}
+
 #ifdef EL_CORE_PROF
 #define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #define EL_PROF(i) { const unsigned long long now = clock64(); prof_acc[i] += now - prof_t; prof_t = now; }
@@ -86,12 +95,14 @@ k_core_ds(const CoreArgs a)
     constexpr int CH = 4 * ROWB / 1024;             // 16-byte chunks per lane in a wavefront's 4 rows
     constexpr int CW16 = DS * 2;                    // byte offset step of a wavefront's column slice
     static_assert(ROWB % 1024 == 0 && KC >= 4 && KC % 4 == 0, "d_m must be a multiple of 512");
+    static_assert(RG == 1 || RG == 2 || RG == 4, "row groups per workgroup");
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
     __shared__ __attribute__((aligned(16))) float Sx[4 * RG * 64 * 4];   // partial scores [wave][rg][lane][4]
     __shared__ __attribute__((aligned(16))) f16_t Px[NB * 32 * 16];      // probabilities [row][t]
     __shared__ float Ax[NB * 32];                                        // per-row rescale factor / final 1/sum
     __shared__ int Fx[4];                                                // per row group: some row rescales
+    __shared__ __attribute__((aligned(1024))) char Dz[ROWB];             // where fetches of rows that do not exist land
 
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -141,6 +152,7 @@ k_core_ds(const CoreArgs a)
     // ---- per-lane LDS offsets inside a tile slot ----
     const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
     const unsigned t_lds = (unsigned)(uintptr_t)Tl;
+    const unsigned dz_lds = (unsigned)(uintptr_t)(const EL_LDS(char) *)Dz;
     int a_base[4];   // score product: row r16, chunk (slice) + 4c + g
     {
         const int fx = tile_swizzle(r16);
@@ -160,163 +172,126 @@ k_core_ds(const CoreArgs a)
         }
     }
 
-    // A wavefront fetches rows 4w..4w+3 of every tile.  Rows at or beyond len are not read.
-    auto issue_dma = [&](int kt, int slot) {
-        const char *sbase = Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB;
-        const int rows_valid = len - (kt * kTileRows16 + 4 * w);     // wave-uniform
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = (i << 2) | w;                               // tile_swizzle(4w + i)
-            const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
-            const unsigned dst = t_lds + slot * SLOT + (4 * w + i) * ROWB;
-            if (i < rows_valid) {
-                if (PIECES == 2) dma_row_2k(dst, voff, sbase);
-                else dma_piece(dst, voff, sbase);
-            }
-        }
-    };
+    // A wavefront fetches rows 4w..4w+3 of every tile, always with the same number of instructions: a row
+    // that does not exist (at or beyond len, or of a tile past this workgroup's range) is replaced by a
+    // fetch of the element's first row into a dump area.  The fetch counter then advances by exactly NI
+    // per tile, and the loop needs neither branches around the requests nor per-tile wait arithmetic.
     auto issue_dma_row = [&](int kt, int slot, int i) {
-        const char *sbase = Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB;
-        const int f = (i << 2) | w;
+        const bool ok = kt < k1 && kt * kTileRows16 + 4 * w + i < len;               // wave-uniform
+        const char *sbase = ok ? Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB : Hb - i * ROWB;
+        const int f = (i << 2) | w;                                                   // tile_swizzle(4w + i)
         const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
-        const unsigned dst = t_lds + slot * SLOT + (4 * w + i) * ROWB;
-        if (kt * kTileRows16 + 4 * w + i < len) {
-            if (PIECES == 2) dma_row_2k(dst, voff, sbase);
-            else dma_piece(dst, voff, sbase);
-        }
-    };
-    auto issue_dma_row_unchecked = [&](int kt, int slot, int i) {
-        const char *sbase = Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB;
-        const int f = (i << 2) | w;
-        const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
-        const unsigned dst = t_lds + slot * SLOT + (4 * w + i) * ROWB;
+        const unsigned dst = ok ? t_lds + slot * SLOT + (4 * w + i) * ROWB : dz_lds;
         if (PIECES == 2) dma_row_2k(dst, voff, sbase);
         else dma_piece(dst, voff, sbase);
     };
-    // all four rows of this wavefront's share of tile kt exist (then exactly NI fetches were issued)
-    auto full_share = [&](int kt) { return (kt * kTileRows16 + 4 * w + 4) <= len; };
+    auto issue_dma = [&](int kt, int slot) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) issue_dma_row(kt, slot, i);
+    };
     // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
-    auto wait_own = [&](int later_full_tiles) {
-        if (later_full_tiles >= 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NI) : "memory");
-        else if (later_full_tiles == 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NI) : "memory");
+    auto wait_own = [&](int later_tiles) {
+        if (later_tiles >= 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NI) : "memory");
+        else if (later_tiles == 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NI) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    // storage dtype -> fp16 in place for one 16-byte chunk of this wavefront's own rows; rows at or
-    // beyond len are written as zeros (their bytes were never fetched)
-    auto convert_chunk = [&](int kt, int slot, int j) {
-        const int off = (4 * w) * ROWB + j * 1024 + l * 16;
-        char *p = T + slot * SLOT + off;
-        const int t = kt * kTileRows16 + off / ROWB;
-        u4 v = u4{0u, 0u, 0u, 0u};
-        if (t < len) {
-            v = *(const u4 *)p;
-            if (BF16) {
-                v.x = bf16x2_to_f16x2_ds(v.x); v.y = bf16x2_to_f16x2_ds(v.y);
-                v.z = bf16x2_to_f16x2_ds(v.z); v.w = bf16x2_to_f16x2_ds(v.w);
-            }
+    // Rows at or beyond len were never fetched and must not reach the MFMAs as garbage: the wavefront that
+    // owns such rows of the (last, ragged) tile kt writes zeros over them.
+    auto zero_ragged = [&](int kt, int slot) {
+        if ((kt + 1) * kTileRows16 <= len) return;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (kt * kTileRows16 + 4 * w + i < len) continue;
+#pragma unroll
+            for (int j = 0; j < PIECES; ++j)
+                *(u4 *)(T + slot * SLOT + (4 * w + i) * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
         }
-        *(u4 *)p = v;
     };
-    // does tile kt need a pass over its bytes at all?  (bf16 always; fp16 only to zero a ragged tail)
-    auto needs_pass = [&](int kt) { return BF16 || (kt + 1) * kTileRows16 > len; };
+    // score-product fragments of one tile: row r16, this wavefront's columns (storage bits)
+    u4 hb[KC];
+    auto load_hb = [&](const EL_LDS(char) *F, int c) { hb[c] = *(const EL_LDS(u4) *)(F + a_base[c & 3] + (c >> 2) * 256); };
 
     EL_PROF_DECL
-#ifdef EL_CORE_PROF
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    EL_PROF(8)
-#endif
-    // ---- prologue: request three tiles, convert the first ----
+    // ---- prologue: request three tiles, wait for the first ----
     if (nloc > 0) {
         issue_dma(k0, 0);
-        if (nloc > 1) issue_dma(k0 + 1, 1);
-        if (nloc > 2) issue_dma(k0 + 2, 2);
-        wait_own((nloc > 1 && full_share(k0 + 1) ? 1 : 0) + (nloc > 2 && full_share(k0 + 2) ? 1 : 0));
-        if (needs_pass(k0)) {
-#pragma unroll
-            for (int j = 0; j < CH; ++j) convert_chunk(k0, 0, j);
-        }
+        issue_dma(k0 + 1, 1);
+        issue_dma(k0 + 2, 2);
+        wait_own(2);
+        zero_ragged(k0, 0);
     }
+    // The compiler does not see the LDS-DMA requests; it does see the ELQ loads above, and would place
+    // their wait (which also drains every later fetch) in front of the first MFMA of EVERY iteration.
+    // Consuming the registers here, on every path into the loop, moves that wait out of it.
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+        for (int c = 0; c < KC; ++c) asm volatile("" :: "v"(elq[rg][c]));
     __syncthreads();
+#pragma unroll
+    for (int c = 0; c < KC; ++c) load_hb(Tl, c);
     EL_PROF(0)
 
+    // Per tile: scores -> B1 -> softmax -> B2 -> weighted sum.  What crosses the barriers:
+    //   B1(k): the partial scores of tile k are in LDS; every wavefront has left the weighted sum of tile
+    //          k-1, so that tile's slot may be refilled (tile k+3 is requested into it after B2(k));
+    //   B2(k): P, rescale factors and flags of tile k are in LDS; every wavefront has waited for its own
+    //          rows of tile k+1, so tile k+1 may be read (its score fragments are requested during the
+    //          weighted sum of tile k and arrive under those MFMAs).
     for (int kk = 0; kk < nloc; ++kk) {
         const int kt = k0 + kk;
         const int slot = kk & 3;
         const EL_LDS(char) *Fl = Tl + slot * SLOT;
-
-        // our rows of tile kk+1 must have landed (tile kk+2 may still fly); tile kk+3 is requested below,
-        // spread over the score loop, into the slot tile kk-1 just left
-        const bool conv_next = (kk + 1 < nloc) && needs_pass(kt + 1);
-        const bool dma_next = kk + 3 < nloc;
-        if (kk + 1 < nloc) wait_own(kk + 2 < nloc && full_share(kt + 2) ? 1 : 0);
+        const EL_LDS(char) *Fn = Tl + ((kk + 1) & 3) * SLOT;
+        const bool more = kk + 1 < nloc;
         EL_PROF(1)
 
-        // ---- partial scores over this wavefront's columns; the conversion of tile kk+1 and the fetch
-        //      requests of tile kk+3 are interleaved with the MFMAs ----
+        // ---- partial scores over this wavefront's columns.  One wavefront per SIMD: the conversion of
+        //      the next fragment is issued behind each MFMA and runs while the matrix unit is busy ----
         f4 sc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) sc[rg] = f4{0.f, 0.f, 0.f, 0.f};
-        // FAST: tile kk+1 needs the conversion pass and all our rows of it exist, tile kk+3 is requested and
-        // all our rows of it exist -- then the loop body has no branches, which matters beyond the branches
-        // themselves: with conditional LDS operations in flight the compiler has to wait for (nearly) all
-        // of them before each use.  Edge tiles take the general body.
-        auto score_block = [&](auto fast_tag) {
-            constexpr bool FAST = decltype(fast_tag)::value;
-            constexpr int CPC = CH / KC;                                  // conversion chunks per k-chunk
-            const int nslot = (kk + 1) & 3;
-            char *cbase = T + nslot * SLOT + (4 * w) * ROWB + l * 16;     // chunk j of our rows: + j * 1024
-            const int trow0 = (kt + 1) * kTileRows16 + 4 * w;
-            const bool do_conv = FAST ? true : conv_next;
-            const bool do_dma = FAST ? true : dma_next;
-            auto ld_cv = [&](int j) {
-                if (FAST) return *(const u4 *)(cbase + j * 1024);
-                return (trow0 + (j * 1024) / ROWB < len) ? *(const u4 *)(cbase + j * 1024) : u4{0u, 0u, 0u, 0u};
-            };
-            // one wavefront per SIMD: nothing else hides LDS latency, so all H fragments of the tile are
-            // requested before the first MFMA
-            h8 hb[KC];
-            u4 cv[2][CPC];
-#pragma unroll
-            for (int c = 0; c < KC; ++c) hb[c] = *(const EL_LDS(h8) *)(Fl + a_base[c & 3] + (c >> 2) * 256);
-            if (do_conv) {
-#pragma unroll
-                for (int e = 0; e < CPC; ++e) cv[0][e] = ld_cv(e);
+        {
+            constexpr int WPM = 4 / RG;                                // words converted per MFMA
+            u4 cur = hb[0];
+            if (BF16) {
+                cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
+                cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
             }
 #pragma unroll
             for (int c = 0; c < KC; ++c) {
-                if (do_conv && c + 1 < KC) {
+                u4 nxt = hb[c + 1 < KC ? c + 1 : c];
 #pragma unroll
-                    for (int e = 0; e < CPC; ++e) cv[(c + 1) & 1][e] = ld_cv((c + 1) * CPC + e);
-                }
-                if (do_dma && (c % (KC / 4)) == 0) {
-                    if (FAST) issue_dma_row_unchecked(kt + 3, (kk + 3) & 3, c / (KC / 4));
-                    else issue_dma_row(kt + 3, (kk + 3) & 3, c / (KC / 4));
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                for (int rg = 0; rg < RG; ++rg) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    sc[rg] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, cur), elq[rg][c], sc[rg], 0, 0, 0);
+                    if (BF16 && c + 1 < KC) {
 #pragma unroll
-                for (int rg = 0; rg < RG; ++rg)
-                    sc[rg] = __builtin_amdgcn_mfma_f32_16x16x32_f16(hb[c], elq[rg][c], sc[rg], 0, 0, 0);
-                if (do_conv) {
-#pragma unroll
-                    for (int e = 0; e < CPC; ++e) {
-                        u4 v = cv[c & 1][e];
-                        if (BF16) {
-                            v.x = bf16x2_to_f16x2_ds(v.x); v.y = bf16x2_to_f16x2_ds(v.y);
-                            v.z = bf16x2_to_f16x2_ds(v.z); v.w = bf16x2_to_f16x2_ds(v.w);
+                        for (int e = 0; e < WPM; ++e) {
+                            nxt[rg * WPM + e] = bf16x2_to_f16x2_ds(nxt[rg * WPM + e]);
+                            asm volatile("" : "+v"(nxt[rg * WPM + e]));       // keeps the conversion behind this MFMA
                         }
-                        *(u4 *)(cbase + (c * CPC + e) * 1024) = v;
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
             }
-        };
-        if (BF16 && kk + 3 < nloc && full_share(kt + 1) && full_share(kt + 3)) score_block(std::true_type{});
-        else score_block(std::false_type{});
+        }
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) *(f4 *)(Sx + ((w * RG + rg) * 64 + l) * 4) = sc[rg];
         EL_PROF(2)
-        __syncthreads();                                              // B1: partial scores are in LDS
+        __syncthreads();                                              // B1
         EL_PROF(3)
+
+        // the first operand blocks of the weighted sum do not depend on the softmax: request them now
+        constexpr int PD = MB < 4 ? MB : 4;                           // transposing reads kept in flight (blocks)
+        s4 tb[PD][2];
+        auto load_tb = [&](int mb) {
+            tb[mb % PD][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_lo[mb & 3] + (mb >> 2) * 256));
+            tb[mb % PD][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_hi[mb & 3] + (mb >> 2) * 256));
+        };
+#pragma unroll
+        for (int mb = 0; mb < PD; ++mb) load_tb(mb);
 
         // ---- softmax bookkeeping of row group w (row = lane%16; its 16 scores sit in 4 lanes x 4 registers) ----
         if (w < RG) {
@@ -348,8 +323,11 @@ k_core_ds(const CoreArgs a)
             if (sq == 0) Ax[16 * w + sr] = alpha;
             if (l == 0) Fx[w] = any_grow ? 1 : 0;
         }
+        // our rows of tile k+1 must have landed before B2 hands the tile over (tile k+2 may still fly)
+        wait_own(1);
+        if (more) zero_ragged(kt + 1, (kk + 1) & 3);
         EL_PROF(4)
-        __syncthreads();                                              // B2: P, rescale factors and flags are in LDS
+        __syncthreads();                                              // B2
         EL_PROF(5)
 
         // ---- weighted sum over this wavefront's columns: X^T[d, r] += sum_t H[t, d] P[r, t] ----
@@ -357,6 +335,9 @@ k_core_ds(const CoreArgs a)
             int any = 0;
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) any |= Fx[rg];
+            h8 P[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) P[nb] = *(const h8 *)(Px + (32 * nb + r32) * 16 + 8 * kg);
             if (any) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
@@ -374,35 +355,50 @@ k_core_ds(const CoreArgs a)
                     }
                 }
             }
-            h8 P[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) P[nb] = *(const h8 *)(Px + (32 * nb + r32) * 16 + 8 * kg);
-            constexpr int PD = MB < 4 ? MB : 4;                          // transposing reads kept in flight (blocks)
-            s4 tb[PD][2];
-#pragma unroll
-            for (int mb = 0; mb < PD; ++mb) {
-                tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_lo[mb & 3] + (mb >> 2) * 256));
-                tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_hi[mb & 3] + (mb >> 2) * 256));
+            // One code path only: a second copy of this block makes the compiler reconcile two versions of
+            // the accumulators where the paths meet, at the price of hundreds of spilled registers.
+            constexpr int WPM = 4 / NB;                                // words converted per MFMA
+            auto packed = [&](int mb) {
+                const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
+                return __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+            };
+            u4 cur = packed(0);
+            if (BF16) {
+                cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
+                cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
             }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
-                const h8 A = __builtin_bit_cast(h8, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+                u4 nxt = packed(mb + 1 < MB ? mb + 1 : mb);
                 __builtin_amdgcn_sched_barrier(0);
-                if (mb + PD < MB) {
-                    tb[mb % PD][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_lo[(mb + PD) & 3] + ((mb + PD) >> 2) * 256));
-                    tb[mb % PD][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_hi[(mb + PD) & 3] + ((mb + PD) >> 2) * 256));
-                }
+                if (mb + PD < MB) load_tb(mb + PD);                    // into the block `cur` came from
+                // the fetch of tile k+3 goes into the slot tile k-1 left before B1
+                if (mb < 4) issue_dma_row(kt + 3, (kk + 3) & 3, mb);
+                // the score fragments of tile k+1, two per block over the second half of the blocks (after
+                // the last tile they read a slot nobody uses)
+                if (mb >= MB / 2) { load_hb(Fn, 2 * (mb - MB / 2)); load_hb(Fn, 2 * (mb - MB / 2) + 1); }
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    X[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, P[nb], X[mb][nb], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    X[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, cur), P[nb], X[mb][nb], 0, 0, 0);
+                    if (BF16 && mb + 1 < MB) {
+#pragma unroll
+                        for (int e = 0; e < WPM; ++e) {
+                            nxt[nb * WPM + e] = bf16x2_to_f16x2_ds(nxt[nb * WPM + e]);
+                            asm volatile("" : "+v"(nxt[nb * WPM + e]));       // keeps the conversion behind this MFMA
+                        }
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
             }
         }
         EL_PROF(6)
-        __syncthreads();          // B3: slot of tile kk is free; the conversions of tile kk+1 are visible
         EL_PROF(7)
     }
+
+    // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- partial result: statistics from the owner wavefronts, X normalised by its own sum ----
     const int parts = a.S, part = s;

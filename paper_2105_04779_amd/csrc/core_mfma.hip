@@ -200,6 +200,11 @@ k_core_mfma(const CoreArgs a)
         stage(true, k0, 0, false, 0, 0);
         __syncthreads();
     }
+    // The compiler does not see the LDS-DMA requests; it does see the ELQ loads above, and would place
+    // their wait (which also drains every later fetch) in front of the first MFMA of EVERY iteration.
+    // Consuming the registers here, on every path into the loop, moves that wait out of it.
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) asm volatile("" :: "v"(elq[c]));
     EL_PROF(0)
 
     for (int kk = 0; kk < nloc; ++kk) {
