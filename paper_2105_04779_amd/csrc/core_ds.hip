@@ -72,17 +72,22 @@ __device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
 }
 
 #ifdef EL_CORE_PROF
-#define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long prof_w0 = wall_clock64(), prof_c0 = prof_t;
 #define EL_PROF(i) { const unsigned long long now = clock64(); prof_acc[i] += now - prof_t; prof_t = now; }
 #else
 #define EL_PROF_DECL
 #define EL_PROF(i)
 #endif
 
-template <int DM, bool BF16, int RG>
+template <int DM, bool BF16_, int RG>
 __global__ void __launch_bounds__(256)
 k_core_ds(const CoreArgs a)
 {
+#ifdef EL_EXP_NOCONV
+    constexpr bool BF16 = false;
+#else
+    constexpr bool BF16 = BF16_;
+#endif
     constexpr int ROWB = DM * 2;                    // bytes per tile row (2-byte elements)
     constexpr int SLOT = kTileRows16 * ROWB;        // one tile
     constexpr int NSLOT = 4;
@@ -99,9 +104,9 @@ k_core_ds(const CoreArgs a)
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
     __shared__ __attribute__((aligned(16))) float Sx[4 * RG * 64 * 4];   // partial scores [wave][rg][lane][4]
-    __shared__ __attribute__((aligned(16))) f16_t Px[NB * 32 * 16];      // probabilities [row][t]
-    __shared__ float Ax[NB * 32];                                        // per-row rescale factor / final 1/sum
-    __shared__ int Fx[4];                                                // per row group: some row rescales
+    __shared__ __attribute__((aligned(16))) f16_t Px[2 * NB * 32 * 16];  // probabilities [tile parity][row][t]
+    __shared__ float Ax[2 * NB * 32];                                    // per-row rescale factor [tile parity][row]
+    __shared__ float Linv[NB * 32];                                      // per-row 1/sum for the partial result
     __shared__ __attribute__((aligned(1024))) char Dz[ROWB];             // where fetches of rows that do not exist land
 
     const int tid = threadIdx.x, l = tid & 63;
@@ -145,9 +150,9 @@ k_core_ds(const CoreArgs a)
             for (int i = 0; i < 16; ++i) X[mb][nb][i] = 0.f;
     float m_ref = -INFINITY, l_sum = 0.f;           // meaningful in owner wavefronts (w < RG) only
 
-    if (tid < NB * 32) Ax[tid] = 1.0f;
-    for (int i = tid; i < NB * 32 * 16; i += 256) Px[i] = (f16_t)0.f;
-    if (tid < 4) Fx[tid] = 0;
+    if (tid < 2 * NB * 32) Ax[tid] = 1.0f;
+    if (tid < NB * 32) Linv[tid] = 0.f;
+    for (int i = tid; i < 2 * NB * 32 * 16; i += 256) Px[i] = (f16_t)0.f;
 
     // ---- per-lane LDS offsets inside a tile slot ----
     const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
@@ -207,17 +212,13 @@ k_core_ds(const CoreArgs a)
                 *(u4 *)(T + slot * SLOT + (4 * w + i) * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
         }
     };
-    // score-product fragments of one tile: row r16, this wavefront's columns (storage bits)
-    u4 hb[KC];
-    auto load_hb = [&](const EL_LDS(char) *F, int c) { hb[c] = *(const EL_LDS(u4) *)(F + a_base[c & 3] + (c >> 2) * 256); };
 
     EL_PROF_DECL
-    // ---- prologue: request three tiles, wait for the first ----
+    // ---- prologue: request two tiles, wait for the first ----
     if (nloc > 0) {
         issue_dma(k0, 0);
         issue_dma(k0 + 1, 1);
-        issue_dma(k0 + 2, 2);
-        wait_own(2);
+        wait_own(1);
         zero_ragged(k0, 0);
     }
     // The compiler does not see the LDS-DMA requests; it does see the ELQ loads above, and would place
@@ -228,173 +229,213 @@ k_core_ds(const CoreArgs a)
 #pragma unroll
         for (int c = 0; c < KC; ++c) asm volatile("" :: "v"(elq[rg][c]));
     __syncthreads();
-#pragma unroll
-    for (int c = 0; c < KC; ++c) load_hb(Tl, c);
     EL_PROF(0)
 
-    // Per tile: scores -> B1 -> softmax -> B2 -> weighted sum.  What crosses the barriers:
-    //   B1(k): the partial scores of tile k are in LDS; every wavefront has left the weighted sum of tile
-    //          k-1, so that tile's slot may be refilled (tile k+3 is requested into it after B2(k));
-    //   B2(k): P, rescale factors and flags of tile k are in LDS; every wavefront has waited for its own
-    //          rows of tile k+1, so tile k+1 may be read (its score fragments are requested during the
-    //          weighted sum of tile k and arrive under those MFMAs).
-    for (int kk = 0; kk < nloc; ++kk) {
-        const int kt = k0 + kk;
-        const int slot = kk & 3;
-        const EL_LDS(char) *Fl = Tl + slot * SLOT;
-        const EL_LDS(char) *Fn = Tl + ((kk + 1) & 3) * SLOT;
-        const bool more = kk + 1 < nloc;
-        EL_PROF(1)
-
-        // ---- partial scores over this wavefront's columns.  One wavefront per SIMD: the conversion of
-        //      the next fragment is issued behind each MFMA and runs while the matrix unit is busy ----
+    // ---- scores of tile kk (slot kk&3) over this wavefront's columns, left in LDS for the exchange.
+    //      The fetch of tile kk+2 is requested between the fragment loads and the first MFMA (it fills
+    //      the LDS latency); the conversion of each next fragment is issued behind an MFMA and runs
+    //      while the matrix unit is busy. ----
+    auto scores = [&](int kk) {
+        const EL_LDS(char) *F = Tl + (kk & 3) * SLOT;
+        u4 hb[KC];
+#pragma unroll
+        for (int c = 0; c < KC; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c & 3] + (c >> 2) * 256);
+        issue_dma(k0 + kk + 2, (kk + 2) & 3);
         f4 sc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) sc[rg] = f4{0.f, 0.f, 0.f, 0.f};
-        {
-            constexpr int WPM = 4 / RG;                                // words converted per MFMA
-            u4 cur = hb[0];
-            if (BF16) {
-                cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
-                cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
-            }
+        constexpr int WPM = 4 / RG;                                    // words converted per MFMA
+        u4 cur = hb[0];
+        if (BF16) {
+            cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
+            cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
+        }
 #pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                u4 nxt = hb[c + 1 < KC ? c + 1 : c];
+        for (int c = 0; c < KC; ++c) {
+            u4 nxt = hb[c + 1 < KC ? c + 1 : c];
 #pragma unroll
-                for (int rg = 0; rg < RG; ++rg) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    sc[rg] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, cur), elq[rg][c], sc[rg], 0, 0, 0);
-                    if (BF16 && c + 1 < KC) {
+            for (int rg = 0; rg < RG; ++rg) {
+                __builtin_amdgcn_sched_barrier(0);
+                sc[rg] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, cur), elq[rg][c], sc[rg], 0, 0, 0);
+                if (BF16 && c + 1 < KC) {
 #pragma unroll
-                        for (int e = 0; e < WPM; ++e) {
-                            nxt[rg * WPM + e] = bf16x2_to_f16x2_ds(nxt[rg * WPM + e]);
-                            asm volatile("" : "+v"(nxt[rg * WPM + e]));       // keeps the conversion behind this MFMA
-                        }
+                    for (int e = 0; e < WPM; ++e) {
+                        nxt[rg * WPM + e] = bf16x2_to_f16x2_ds(nxt[rg * WPM + e]);
+                        asm volatile("" : "+v"(nxt[rg * WPM + e]));           // keeps the conversion behind this MFMA
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                cur = nxt;
             }
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
         }
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) *(f4 *)(Sx + ((w * RG + rg) * 64 + l) * 4) = sc[rg];
-        EL_PROF(2)
-        __syncthreads();                                              // B1
-        EL_PROF(3)
+    };
 
-        // the first operand blocks of the weighted sum do not depend on the softmax: request them now
-        constexpr int PD = MB < 4 ? MB : 4;                           // transposing reads kept in flight (blocks)
-        s4 tb[PD][2];
-        auto load_tb = [&](int mb) {
-            tb[mb % PD][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_lo[mb & 3] + (mb >> 2) * 256));
-            tb[mb % PD][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(Fl + b_hi[mb & 3] + (mb >> 2) * 256));
+    // ---- softmax bookkeeping of row group w for one tile, cut into stages that the weighted sum of the
+    //      previous tile interleaves with its MFMAs.  Lane = 4 * row + q holds positions 4q..4q+3 of its
+    //      row, so a row's statistics stay inside a quad.  Everything is branch-free: a row whose maximum
+    //      does not grow gets the factor exp2(0) = 1. ----
+    const bool owner = RG == 4 || w < RG;
+    const int sr = l >> 2, sq = l & 3;
+    f4 st0, st1, st2, st3;
+    float sv[4], pr[4], mx_l = 0.f, alpha = 1.f;
+    auto sm_load = [&]() {
+        if (!owner) return;
+        const int src_lane = sr + 16 * sq;
+        st0 = *(const f4 *)(Sx + ((0 * RG + w) * 64 + src_lane) * 4); st1 = *(const f4 *)(Sx + ((1 * RG + w) * 64 + src_lane) * 4);
+        st2 = *(const f4 *)(Sx + ((2 * RG + w) * 64 + src_lane) * 4); st3 = *(const f4 *)(Sx + ((3 * RG + w) * 64 + src_lane) * 4);
+    };
+    auto sm_stage1 = [&](int kt) {                                    // sum of the four partials, local maximum
+        if (!owner) return;
+        const int lim = len - kt * kTileRows16 - 4 * sq;                // positions at or beyond len do not exist
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sv[j] = (st0[j] + st1[j]) + (st2[j] + st3[j]);
+            sv[j] = j < lim ? sv[j] : -INFINITY;
+        }
+        mx_l = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+    };
+    auto sm_stage2 = [&]() {                                          // row maximum, reference, rescale factor
+        if (!owner) return;
+        float mx = fmaxf(mx_l, quad_xor1(mx_l));
+        mx = fmaxf(mx, quad_xor2(mx));
+        const float m_new = mx > m_ref + kRescaleStep16 ? mx : m_ref;   // also on the first tile (m_ref = -inf)
+        alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        m_ref = m_new;
+    };
+    auto sm_stage3 = [&]() {                                          // probabilities and running sum
+        if (!owner) return;
+        l_sum *= alpha;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
+    };
+    auto sm_stage4 = [&](int buf) {                                   // publish P (fp16, RNE) and the factors
+        if (!owner) return;
+        const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
+        *(h4 *)(Px + buf * (NB * 32 * 16) + (16 * w + sr) * 16 + 4 * sq) = h4{p01[0], p01[1], p23[0], p23[1]};
+        if (sq == 0) Ax[buf * (NB * 32) + 16 * w + sr] = alpha;
+    };
+
+    // ---- weighted sum of tile kk over this wavefront's columns: X^T[d, r] += sum_t H[t, d] P[r, t];
+    //      with SM, the softmax stages of tile kk+1 ride between its MFMAs ----
+    constexpr int PD = MB < 4 ? MB : 4;                               // transposing reads kept in flight (blocks)
+    s4 tb[PD][2];
+    h8 P[NB];
+    float al[NB];
+    auto pv_loads = [&](int kk) {                                     // operands that do not depend on the barrier
+        const EL_LDS(char) *F = Tl + (kk & 3) * SLOT;
+        const int buf = kk & 1;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            P[nb] = *(const h8 *)(Px + buf * (NB * 32 * 16) + (32 * nb + r32) * 16 + 8 * kg);
+            al[nb] = Ax[buf * (NB * 32) + 32 * nb + r32];
+        }
+#pragma unroll
+        for (int mb = 0; mb < PD; ++mb) {
+            tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
+            tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
+        }
+    };
+    auto pv = [&](int kk, auto sm_tag) {
+        constexpr bool SM = decltype(sm_tag)::value;
+        const EL_LDS(char) *F = Tl + (kk & 3) * SLOT;
+        const int kt_next = k0 + kk + 1;
+        if (SM) sm_load();
+        bool resc = al[0] != 1.0f;
+        if (NB > 1) resc = resc || al[NB - 1] != 1.0f;
+        if (__any(resc)) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    // one accumulator tuple at a time through arch VGPRs; the empty asm statements pin
+                    // the register classes so the allocator does not move the whole array at once
+                    f16v t = X[mb][nb];
+                    asm volatile("" : "+v"(t));
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) t[i] *= al[nb];
+                    asm volatile("" : "+a"(t));
+                    X[mb][nb] = t;
+                }
+            }
+        }
+        constexpr int WPM = 4 / NB;                                    // words converted per MFMA
+        constexpr int S0 = MB >= 8 ? 1 : 0;                            // block after which softmax stage 1 runs
+        auto packed = [&](int mb) {
+            const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
+            return __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
         };
-#pragma unroll
-        for (int mb = 0; mb < PD; ++mb) load_tb(mb);
-
-        // ---- softmax bookkeeping of row group w (row = lane%16; its 16 scores sit in 4 lanes x 4 registers) ----
-        if (w < RG) {
-            // lane = 4 * row + q holds positions 4q..4q+3 of its row: the row's statistics stay inside a quad
-            const int sr = l >> 2, sq = l & 3, src_lane = sr + 16 * sq;
-            f4 t0 = *(const f4 *)(Sx + ((0 * RG + w) * 64 + src_lane) * 4), t1 = *(const f4 *)(Sx + ((1 * RG + w) * 64 + src_lane) * 4);
-            f4 t2 = *(const f4 *)(Sx + ((2 * RG + w) * 64 + src_lane) * 4), t3 = *(const f4 *)(Sx + ((3 * RG + w) * 64 + src_lane) * 4);
-            float sv[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) sv[j] = (t0[j] + t1[j]) + (t2[j] + t3[j]);
-            if ((kt + 1) * kTileRows16 > len) {      // ragged last tile: positions at or beyond len do not exist
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (kt * kTileRows16 + 4 * sq + j >= len) sv[j] = -INFINITY;
-            }
-            float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-            mx = fmaxf(mx, quad_xor1(mx));
-            mx = fmaxf(mx, quad_xor2(mx));
-            const bool grow = mx > m_ref + kRescaleStep16;   // also true on the first tile (m_ref = -inf)
-            const bool any_grow = __any(grow);
-            float alpha = 1.0f;
-            if (grow) { alpha = __builtin_amdgcn_exp2f(m_ref - mx); m_ref = mx; }
-            l_sum *= alpha;
-            float pr[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
-            const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
-            *(h4 *)(Px + (16 * w + sr) * 16 + 4 * sq) = h4{p01[0], p01[1], p23[0], p23[1]};
-            if (sq == 0) Ax[16 * w + sr] = alpha;
-            if (l == 0) Fx[w] = any_grow ? 1 : 0;
+        u4 cur = packed(0);
+        if (BF16) {
+            cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
+            cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
         }
-        // our rows of tile k+1 must have landed before B2 hands the tile over (tile k+2 may still fly)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            u4 nxt = packed(mb + 1 < MB ? mb + 1 : mb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (mb + PD < MB) {                                        // into the block `cur` came from
+                tb[mb % PD][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[(mb + PD) & 3] + ((mb + PD) >> 2) * 256));
+                tb[mb % PD][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[(mb + PD) & 3] + ((mb + PD) >> 2) * 256));
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                __builtin_amdgcn_sched_barrier(0);
+                X[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, cur), P[nb], X[mb][nb], 0, 0, 0);
+                if (BF16 && mb + 1 < MB) {
+#pragma unroll
+                    for (int e = 0; e < WPM; ++e) {
+                        nxt[nb * WPM + e] = bf16x2_to_f16x2_ds(nxt[nb * WPM + e]);
+                        asm volatile("" : "+v"(nxt[nb * WPM + e]));           // keeps the conversion behind this MFMA
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (SM) {
+                if (mb == S0) sm_stage1(kt_next);
+                if (mb == S0 + 1) sm_stage2();
+                if (mb == S0 + 2) sm_stage3();
+                if (mb == S0 + 3) sm_stage4((kk + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            cur = nxt;
+        }
+    };
+
+    // Tile j's scores and softmax run one tile ahead of its weighted sum.  What crosses the barriers:
+    //   B1(j): the partial scores of tile j are in LDS;
+    //   B2(j): P and the rescale factors of tile j are in LDS (buffer j&1; the weighted sum of tile j-1
+    //          took its operands from the other buffer before B1(j)); every wavefront has left the
+    //          weighted sum of tile j-1, so that tile's slot may be refilled (tile j+3 goes there, requested
+    //          at the start of the scores of tile j+1), and has waited for its own rows of tile j+1.
+    if (nloc > 0) {
+        scores(0);
+        EL_PROF(2)
+        __syncthreads();                                              // B1(0)
+        EL_PROF(3)
+        sm_load(); sm_stage1(k0); sm_stage2(); sm_stage3(); sm_stage4(0);
         wait_own(1);
-        if (more) zero_ragged(kt + 1, (kk + 1) & 3);
+        if (nloc > 1) zero_ragged(k0 + 1, 1);
         EL_PROF(4)
-        __syncthreads();                                              // B2
+        __syncthreads();                                              // B2(0)
         EL_PROF(5)
-
-        // ---- weighted sum over this wavefront's columns: X^T[d, r] += sum_t H[t, d] P[r, t] ----
-        {
-            int any = 0;
-#pragma unroll
-            for (int rg = 0; rg < RG; ++rg) any |= Fx[rg];
-            h8 P[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) P[nb] = *(const h8 *)(Px + (32 * nb + r32) * 16 + 8 * kg);
-            if (any) {
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const float alpha = Ax[32 * nb + r32];
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        // one accumulator tuple at a time through arch VGPRs; the empty asm statements pin
-                        // the register classes so the allocator does not move the whole array at once
-                        f16v t = X[mb][nb];
-                        asm volatile("" : "+v"(t));
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) t[i] *= alpha;
-                        asm volatile("" : "+a"(t));
-                        X[mb][nb] = t;
-                    }
-                }
-            }
-            // One code path only: a second copy of this block makes the compiler reconcile two versions of
-            // the accumulators where the paths meet, at the price of hundreds of spilled registers.
-            constexpr int WPM = 4 / NB;                                // words converted per MFMA
-            auto packed = [&](int mb) {
-                const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
-                return __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-            };
-            u4 cur = packed(0);
-            if (BF16) {
-                cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
-                cur.z = bf16x2_to_f16x2_ds(cur.z); cur.w = bf16x2_to_f16x2_ds(cur.w);
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                u4 nxt = packed(mb + 1 < MB ? mb + 1 : mb);
-                __builtin_amdgcn_sched_barrier(0);
-                if (mb + PD < MB) load_tb(mb + PD);                    // into the block `cur` came from
-                // the fetch of tile k+3 goes into the slot tile k-1 left before B1
-                if (mb < 4) issue_dma_row(kt + 3, (kk + 3) & 3, mb);
-                // the score fragments of tile k+1, two per block over the second half of the blocks (after
-                // the last tile they read a slot nobody uses)
-                if (mb >= MB / 2) { load_hb(Fn, 2 * (mb - MB / 2)); load_hb(Fn, 2 * (mb - MB / 2) + 1); }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    X[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, cur), P[nb], X[mb][nb], 0, 0, 0);
-                    if (BF16 && mb + 1 < MB) {
-#pragma unroll
-                        for (int e = 0; e < WPM; ++e) {
-                            nxt[nb * WPM + e] = bf16x2_to_f16x2_ds(nxt[nb * WPM + e]);
-                            asm volatile("" : "+v"(nxt[nb * WPM + e]));       // keeps the conversion behind this MFMA
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                cur = nxt;
-            }
+        for (int kk = 1; kk < nloc; ++kk) {
+            scores(kk);
+            pv_loads(kk - 1);
+            EL_PROF(2)
+            __syncthreads();                                          // B1(kk)
+            EL_PROF(3)
+            pv(kk - 1, std::true_type{});
+            wait_own(1);
+            if (kk + 1 < nloc) zero_ragged(k0 + kk + 1, (kk + 1) & 3);
+            EL_PROF(6)
+            __syncthreads();                                          // B2(kk)
+            EL_PROF(7)
         }
-        EL_PROF(6)
-        EL_PROF(7)
+        pv_loads(nloc - 1);
+        pv(nloc - 1, std::false_type{});
+        EL_PROF(1)
     }
 
     // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
@@ -407,7 +448,7 @@ k_core_ds(const CoreArgs a)
         l_sum += quad_xor2(l_sum);
         const int sr = l >> 2, row = row0 + 16 * w + sr;
         if ((l & 3) == 0) {
-            Ax[16 * w + sr] = l_sum > 0.f ? 1.0f / l_sum : 0.f;
+            Linv[16 * w + sr] = l_sum > 0.f ? 1.0f / l_sum : 0.f;
             if (row < a.R) {
                 float *ml_out = a.ML + (((size_t)b * parts + part) * a.Rs + row) * 2;
                 ml_out[0] = m_ref; ml_out[1] = l_sum;
@@ -422,7 +463,7 @@ k_core_ds(const CoreArgs a)
     // banks), then every wavefront writes 16 rows, 1 KB per store instruction
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const float inv = Ax[32 * nb + r32];
+        const float inv = Linv[32 * nb + r32];
         const int srow = 32 * nb + r32;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -458,6 +499,8 @@ k_core_ds(const CoreArgs a)
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
         for (int i = 0; i < 12; ++i) a.prof[i] = prof_acc[i];
         a.prof[12] = (unsigned long long)nloc;
+        a.prof[13] = wall_clock64() - prof_w0;
+        a.prof[14] = clock64() - prof_c0;
     }
 #endif
 }
