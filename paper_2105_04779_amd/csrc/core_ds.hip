@@ -71,12 +71,19 @@ __device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
     return __builtin_bit_cast(h8, x);
 }
 
-#ifdef EL_CORE_PROF
+#if defined(EL_CORE_PROF) && !defined(EL_CORE_TS)
 #define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long prof_w0 = wall_clock64(), prof_c0 = prof_t;
 #define EL_PROF(i) { const unsigned long long now = clock64(); prof_acc[i] += now - prof_t; prof_t = now; }
 #else
 #define EL_PROF_DECL
 #define EL_PROF(i)
+#endif
+#ifdef EL_CORE_TS
+#define EL_TS_DECL unsigned long long ts[12], ts_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long ts_w0 = wall_clock64(), ts_c0 = clock64();
+#define EL_TS(i) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_memtime %0" : "=s"(ts[i])); __builtin_amdgcn_sched_barrier(0); }
+#else
+#define EL_TS_DECL
+#define EL_TS(i)
 #endif
 
 template <int DM, bool BF16_, int RG>
@@ -129,25 +136,6 @@ k_core_ds(const CoreArgs a)
     const int nloc = k1 - k0;
     const char *Hb = (const char *)a.H + (size_t)b * a.h_stride * 2;
 
-    // ---- this wavefront's column slice of ELQ, all row groups: B operand of the score product ----
-    h8 elq[RG][KC];
-#pragma unroll
-    for (int rg = 0; rg < RG; ++rg) {
-        const int row = row0 + 16 * rg + r16;
-        // pad rows (row >= R) are never written by the expansion step: they read as zero here
-        const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + DS * w + 8 * g;
-        const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int c = 0; c < KC; ++c) elq[rg][c] = row < a.R ? *(const h8 *)(src + 32 * c) : zero;
-    }
-
-    f16v X[MB][NB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) X[mb][nb][i] = 0.f;
     float m_ref = -INFINITY, l_sum = 0.f;           // meaningful in owner wavefronts (w < RG) only
 
     if (tid < 2 * NB * 32) Ax[tid] = 1.0f;
@@ -214,13 +202,33 @@ k_core_ds(const CoreArgs a)
     };
 
     EL_PROF_DECL
+    EL_TS_DECL
     // ---- prologue: request two tiles, wait for the first ----
+    // the first two tiles are requested before anything else is: they take the longest to arrive
     if (nloc > 0) {
         issue_dma(k0, 0);
         issue_dma(k0 + 1, 1);
-        wait_own(1);
-        zero_ragged(k0, 0);
     }
+
+    // ---- this wavefront's column slice of ELQ, all row groups: B operand of the score product ----
+    h8 elq[RG][KC];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+        const int row = row0 + 16 * rg + r16;
+        // pad rows (row >= R) are never written by the expansion step: they read as zero here
+        const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + DS * w + 8 * g;
+        const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < KC; ++c) elq[rg][c] = row < a.R ? *(const h8 *)(src + 32 * c) : zero;
+    }
+
+    f16v X[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) X[mb][nb][i] = 0.f;
     // The compiler does not see the LDS-DMA requests; it does see the ELQ loads above, and would place
     // their wait (which also drains every later fetch) in front of the first MFMA of EVERY iteration.
     // Consuming the registers here, on every path into the loop, moves that wait out of it.
@@ -228,6 +236,8 @@ k_core_ds(const CoreArgs a)
     for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
         for (int c = 0; c < KC; ++c) asm volatile("" :: "v"(elq[rg][c]));
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  // ELQ and, requested before it, both tiles
+    if (nloc > 0) zero_ragged(k0, 0);
     __syncthreads();
     EL_PROF(0)
 
@@ -240,7 +250,9 @@ k_core_ds(const CoreArgs a)
         u4 hb[KC];
 #pragma unroll
         for (int c = 0; c < KC; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c & 3] + (c >> 2) * 256);
+        EL_TS(1)
         issue_dma(k0 + kk + 2, (kk + 2) & 3);
+        EL_TS(2)
         f4 sc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) sc[rg] = f4{0.f, 0.f, 0.f, 0.f};
@@ -268,8 +280,10 @@ k_core_ds(const CoreArgs a)
             __builtin_amdgcn_sched_barrier(0);
             cur = nxt;
         }
+        EL_TS(3)
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) *(f4 *)(Sx + ((w * RG + rg) * 64 + l) * 4) = sc[rg];
+        EL_TS(4)
     };
 
     // ---- softmax bookkeeping of row group w for one tile, cut into stages that the weighted sum of the
@@ -301,7 +315,8 @@ k_core_ds(const CoreArgs a)
         float mx = fmaxf(mx_l, quad_xor1(mx_l));
         mx = fmaxf(mx, quad_xor2(mx));
         const float m_new = mx > m_ref + kRescaleStep16 ? mx : m_ref;   // also on the first tile (m_ref = -inf)
-        alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
+        alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
         m_ref = m_new;
     };
     auto sm_stage3 = [&]() {                                          // probabilities and running sum
@@ -360,12 +375,13 @@ k_core_ds(const CoreArgs a)
                 }
             }
         }
-        constexpr int WPM = 4 / NB;                                    // words converted per MFMA
+        EL_TS(7)
         constexpr int S0 = MB >= 8 ? 1 : 0;                            // block after which softmax stage 1 runs
         auto packed = [&](int mb) {
             const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
             return __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
         };
+        constexpr int WPM = 4 / NB;                                    // words converted per MFMA
         u4 cur = packed(0);
         if (BF16) {
             cur.x = bf16x2_to_f16x2_ds(cur.x); cur.y = bf16x2_to_f16x2_ds(cur.y);
@@ -401,6 +417,7 @@ k_core_ds(const CoreArgs a)
             }
             cur = nxt;
         }
+        EL_TS(8)
     };
 
     // Tile j's scores and softmax run one tile ahead of its weighted sum.  What crosses the barriers:
@@ -421,17 +438,25 @@ k_core_ds(const CoreArgs a)
         __syncthreads();                                              // B2(0)
         EL_PROF(5)
         for (int kk = 1; kk < nloc; ++kk) {
+            EL_TS(0)
             scores(kk);
             pv_loads(kk - 1);
             EL_PROF(2)
+            EL_TS(5)
             __syncthreads();                                          // B1(kk)
             EL_PROF(3)
+            EL_TS(6)
             pv(kk - 1, std::true_type{});
             wait_own(1);
             if (kk + 1 < nloc) zero_ragged(k0 + kk + 1, (kk + 1) & 3);
             EL_PROF(6)
+            EL_TS(9)
             __syncthreads();                                          // B2(kk)
             EL_PROF(7)
+            EL_TS(10)
+#ifdef EL_CORE_TS
+            for (int i = 0; i < 10; ++i) ts_acc[i] += ts[i + 1] - ts[i];
+#endif
         }
         pv_loads(nloc - 1);
         pv(nloc - 1, std::false_type{});
@@ -493,7 +518,15 @@ k_core_ds(const CoreArgs a)
             *(h8 *)(x_out + (size_t)srow * DM + hf * 512 + 8 * l) = h8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
         }
     }
-#ifdef EL_CORE_PROF
+#ifdef EL_CORE_TS
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
+        for (int i = 0; i < 10; ++i) a.prof[i] = ts_acc[i];
+        a.prof[12] = (unsigned long long)(nloc > 1 ? nloc - 1 : 1);
+        a.prof[13] = wall_clock64() - ts_w0;
+        a.prof[14] = clock64() - ts_c0;
+    }
+#endif
+#if defined(EL_CORE_PROF) && !defined(EL_CORE_TS)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     EL_PROF(11)
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
