@@ -143,6 +143,9 @@ el_status el_attn_prepare(const el_attn_config *cfg,
 
     hipStream_t s = (hipStream_t)stream;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return EL_ERR_HIP; }
+    if (hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->num_cus < 1) {
+        delete c; return EL_ERR_HIP;
+    }
 
     const size_t es = dtype_size(cfg->dtype);
     const size_t wbytes = (size_t)cfg->d_model * c->hd * es;
@@ -245,7 +248,7 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
 
     if (el_attn_uses_mfma(ctx)) {
-        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override);
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus);
         // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
         const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
         if (ctx->use_mfma_gemm) {
@@ -265,7 +268,7 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
         }
         if (ctx->use_mfma_gemm) {
             // merge of the partials fused into a6, then a7
-            if (launch_vproj_mfma(ctx, p, ws, pl.parts, pl.Rs, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_vproj_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
             if (launch_oproj_mfma(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
             return EL_OK;
         }

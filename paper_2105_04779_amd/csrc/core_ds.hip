@@ -104,7 +104,6 @@ k_core_ds(const CoreArgs a)
     constexpr int KC = DS / 32;                     // k-chunks of the score product
     constexpr int MB = DS / 32;                     // 32-column blocks of the output
     constexpr int NB = (RG + 1) / 2;                // 32-row blocks of expanded queries
-    constexpr int CH = 4 * ROWB / 1024;             // 16-byte chunks per lane in a wavefront's 4 rows
     constexpr int CW16 = DS * 2;                    // byte offset step of a wavefront's column slice
     static_assert(ROWB % 1024 == 0 && KC >= 4 && KC % 4 == 0, "d_m must be a multiple of 512");
     static_assert(RG == 1 || RG == 2 || RG == 4, "row groups per workgroup");
@@ -125,45 +124,19 @@ k_core_ds(const CoreArgs a)
     const int id = blockIdx.x;
     const int oct = id / (8 * a.nblocks), rem = id % (8 * a.nblocks);
     const int rb = rem >> 3, group = oct * 8 + (rem & 7);
+    const int row0 = rb * (16 * RG);                 // first expanded-query row of this workgroup
     if (group >= a.B * a.S) return;
     const int b = group / a.S, s = group % a.S;
-    const int row0 = rb * (16 * RG);                 // first expanded-query row of this workgroup
-
     int len = a.lengths ? a.lengths[b] : a.n;
     len = min(max(len, 1), a.n);
     const int NT = (len + kTileRows16 - 1) / kTileRows16;
-    const int k0 = (int)(((int64_t)NT * s) / a.S), k1 = (int)(((int64_t)NT * (s + 1)) / a.S);
+    const int k0 = (NT * s) / a.S, k1 = (NT * (s + 1)) / a.S;   // NT * S stays far below 2^31
     const int nloc = k1 - k0;
     const char *Hb = (const char *)a.H + (size_t)b * a.h_stride * 2;
 
-    float m_ref = -INFINITY, l_sum = 0.f;           // meaningful in owner wavefronts (w < RG) only
-
-    if (tid < 2 * NB * 32) Ax[tid] = 1.0f;
-    if (tid < NB * 32) Linv[tid] = 0.f;
-    for (int i = tid; i < 2 * NB * 32 * 16; i += 256) Px[i] = (f16_t)0.f;
-
-    // ---- per-lane LDS offsets inside a tile slot ----
     const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
     const unsigned t_lds = (unsigned)(uintptr_t)Tl;
     const unsigned dz_lds = (unsigned)(uintptr_t)(const EL_LDS(char) *)Dz;
-    int a_base[4];   // score product: row r16, chunk (slice) + 4c + g
-    {
-        const int fx = tile_swizzle(r16);
-#pragma unroll
-        for (int ci = 0; ci < 4; ++ci) a_base[ci] = r16 * ROWB + CW16 * w + (((4 * ci + g) ^ fx) << 4);
-    }
-    int b_lo[4], b_hi[4];   // weighted sum: lane i = 4k+q of 16-lane block (dh, kg) reads row 8kg+k (+4), columns 32mb+16dh+4q..+3
-    {
-        const int dh = g & 1, k = r16 >> 2, q = r16 & 3;
-        const int t_lo = 8 * kg + k, t_hi = t_lo + 4;
-        const int f_lo = tile_swizzle(t_lo), f_hi = tile_swizzle(t_hi);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            const int cl = 4 * mi + 2 * dh + (q >> 1);
-            b_lo[mi] = t_lo * ROWB + CW16 * w + ((cl ^ f_lo) << 4) + (q & 1) * 8;
-            b_hi[mi] = t_hi * ROWB + CW16 * w + ((cl ^ f_hi) << 4) + (q & 1) * 8;
-        }
-    }
 
     // A wavefront fetches rows 4w..4w+3 of every tile, always with the same number of instructions: a row
     // that does not exist (at or beyond len, or of a tile past this workgroup's range) is replaced by a
@@ -208,6 +181,32 @@ k_core_ds(const CoreArgs a)
     if (nloc > 0) {
         issue_dma(k0, 0);
         issue_dma(k0 + 1, 1);
+    }
+
+    float m_ref = -INFINITY, l_sum = 0.f;           // meaningful in owner wavefronts (w < RG) only
+
+    if (tid < 2 * NB * 32) Ax[tid] = 1.0f;
+    if (tid < NB * 32) Linv[tid] = 0.f;
+    for (int i = tid; i < 2 * NB * 32 * 16; i += 256) Px[i] = (f16_t)0.f;
+
+    // ---- per-lane LDS offsets inside a tile slot ----
+    int a_base[4];   // score product: row r16, chunk (slice) + 4c + g
+    {
+        const int fx = tile_swizzle(r16);
+#pragma unroll
+        for (int ci = 0; ci < 4; ++ci) a_base[ci] = r16 * ROWB + CW16 * w + (((4 * ci + g) ^ fx) << 4);
+    }
+    int b_lo[4], b_hi[4];   // weighted sum: lane i = 4k+q of 16-lane block (dh, kg) reads row 8kg+k (+4), columns 32mb+16dh+4q..+3
+    {
+        const int dh = g & 1, k = r16 >> 2, q = r16 & 3;
+        const int t_lo = 8 * kg + k, t_hi = t_lo + 4;
+        const int f_lo = tile_swizzle(t_lo), f_hi = tile_swizzle(t_hi);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            const int cl = 4 * mi + 2 * dh + (q >> 1);
+            b_lo[mi] = t_lo * ROWB + CW16 * w + ((cl ^ f_lo) << 4) + (q & 1) * 8;
+            b_hi[mi] = t_hi * ROWB + CW16 * w + ((cl ^ f_hi) << 4) + (q & 1) * 8;
+        }
     }
 
     // ---- this wavefront's column slice of ELQ, all row groups: B operand of the score product ----

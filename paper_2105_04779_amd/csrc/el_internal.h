@@ -97,6 +97,7 @@ struct el_attn_ctx {
     int use_mfma_core;      // MFMA attention core available for this (dtype, d_m)
     int use_mfma_gemm;      // MFMA projection GEMMs available for this (dtype, d_m, d_k)
     int device;
+    int num_cus;            // compute units of that device
     // optional event pairs around the core kernel (measurement aid)
     hipEvent_t *ev;         // 2 * ev_cap events, or null
     int ev_cap, ev_used;
@@ -132,10 +133,10 @@ struct CorePlan {
     int nblocks;  // row blocks (workgroups sharing one H range)
     int Rs;       // padded row count of ELQ / partial buffers = nblocks * 16 * nrg
     int S;        // contiguous key-range splits per batch element
-    int parts;    // partial results per (batch element, row) = S * 4 / nrg
+    int parts;    // partial results per (batch element, row) = S
 };
 bool core_mfma_supported(int dtype, int d_m);
-CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override);
+CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus);
 hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_merge_exp2(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
@@ -146,7 +147,7 @@ hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hi
 hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s);
 hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, float scale, hipStream_t s);
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s);
-hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs, hipStream_t s);
+hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
 
 } // namespace el

@@ -141,6 +141,38 @@ k_gemm_nt(const GemmArgs g)
                 acc[t][0] += o[0]; acc[t][1] += o[1]; acc[t][2] += o[2]; acc[t][3] += o[3];
             }
     }
+    // One tile row per workgroup (WM == 1, no K split, fp16 out, no bias): the 16 x (64 NT WN) tile goes
+    // through LDS so that every store instruction writes whole 1 KB runs of one output row instead
+    // of 32-byte pieces of sixteen rows.
+    if constexpr (KS == 1 && WM == 1 && CK == C_F16) {
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        constexpr int TW = 16 * NT * WN;                  // tile width in columns
+        static_assert(TW % 512 == 0, "rows are written in 1 KB runs");
+        __shared__ __attribute__((aligned(16))) _Float16 Ct[16 * (TW + 8)];   // +8: rows start 16 bytes apart in the banks
+        if (live) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int col = (wt % WN) * 16 * NT + 16 * t + 4 * q4;
+                *(h4 *)(Ct + r16 * (TW + 8) + col) = h4{(_Float16)(acc[t][0] * g.scale), (_Float16)(acc[t][1] * g.scale),
+                                                          (_Float16)(acc[t][2] * g.scale), (_Float16)(acc[t][3] * g.scale)};
+            }
+        }
+        __syncthreads();
+        const int nb0 = blockIdx.x * TW;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 4 * w + i, mm = blockIdx.y * 16 + row;
+            if (mm >= g.M) continue;
+            const size_t c_row = (size_t)(mm / g.x) * g.c_rB + (size_t)(mm % g.x) * g.c_rJ + (size_t)z * g.c_rI;
+#pragma unroll
+            for (int hf = 0; hf < TW / 512; ++hf) {
+                const int col = hf * 512 + 8 * l;
+                if (nb0 + col >= g.N) continue;          // N is a multiple of 8 on this path (checked by the host)
+                *(h8 *)((f16_t *)g.C + c_row * g.ldc + (size_t)g.c_col_z * z + nb0 + col) = *(const h8 *)(Ct + row * (TW + 8) + col);
+            }
+        }
+        return;
+    }
     if (!live) return;
 
     // C^T layout of the MFMA: this lane holds output row m0 + l%16, columns n0 + 16t + 4*q4 + j (j = 0..3)
@@ -306,19 +338,38 @@ k_vproj_slab(const GemmArgs g)
     }
 
     // ---- merged activation rows 4w..4w+3 ----
-    // Step 1: the log-sum-exp weights of the four rows, one (row, part) pair per lane so that all
-    // statistics are fetched in a single round trip; lane 16*row + part keeps the normalised weight.
-    float wgt_lane;
+    // Everything this needs is requested before anything is used: the statistics (one (row, part) pair
+    // per lane), then all partial rows (four rows x the slots in use x both halves), so the whole merge
+    // costs one round trip to memory.
+    constexpr int HF = ROWB / 1024;
+    auto row_src = [&](int ii, int p, int hf) {
+        const int m = min(m0 + 4 * w + ii, g.M - 1);
+        const int b = m / g.x, r = head * g.x + (m % g.x);
+        return (const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + hf * 512 + 8 * l);
+    };
+    float mp, lp;
     {
         const int ii = l >> 4, p = l & 15;
         const int m = min(m0 + 4 * w + ii, g.M - 1);
         const int b = m / g.x, r = head * g.x + (m % g.x);
-        float mp = -INFINITY, lp = 0.f;
-        if (p < g.parts) {
-            const float *ml = g.ML + (((size_t)b * g.parts + p) * g.Rs + r) * 2;
-            lp = ml[1];
-            if (lp > 0.f) mp = ml[0];
-        }
+        const float *ml = g.ML + (((size_t)b * g.parts + min(p, g.parts - 1)) * g.Rs + r) * 2;
+        mp = ml[0]; lp = ml[1];
+        if (p >= g.parts) lp = 0.f;
+    }
+
+    h8 xv[4][HF][kMaxParts];
+#pragma unroll
+    for (int pp = 0; pp < kMaxParts; ++pp) {
+        if (pp >= g.parts) continue;                     // uniform
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+            for (int hf = 0; hf < HF; ++hf)
+                xv[ii][hf][pp] = *row_src(ii, pp, hf);
+    }
+    float wgt_lane;
+    {
+        if (!(lp > 0.f)) { lp = 0.f; mp = -INFINITY; }       // an empty part (its maximum was never written)
         float Mx = mp;
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) Mx = fmaxf(Mx, __shfl_xor(Mx, o, 64));
@@ -328,56 +379,32 @@ k_vproj_slab(const GemmArgs g)
         for (int o = 1; o < 16; o <<= 1) den += __shfl_xor(den, o, 64);
         wgt_lane = den > 0.f ? wp / den : 0.f;
     }
-    // Step 2: the rows themselves, two in flight at a time (each row: all parts, both halves).
-    {
-        constexpr int HF = ROWB / 1024;
-        auto row_src = [&](int ii, int p, int hf) {
-            const int m = min(m0 + 4 * w + ii, g.M - 1);
-            const int b = m / g.x, r = head * g.x + (m % g.x);
-            return (const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + hf * 512 + 8 * l);
-        };
-        h8 xv[2][HF][4];                               // up to four parts per pass
-        for (int p0 = 0; p0 < g.parts; p0 += 4) {
-            auto load_row = [&](int ii, h8 (*dst)[4]) {
 #pragma unroll
-                for (int hf = 0; hf < HF; ++hf)
+    for (int ii = 0; ii < 4; ++ii) {
+        const int ar = 4 * w + ii;
+        float wrow[kMaxParts];
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp)
-                        if (p0 + pp < g.parts) dst[hf][pp] = *row_src(ii, p0 + pp, hf);
-            };
-            load_row(0, xv[0]);
+        for (int pp = 0; pp < kMaxParts; ++pp) {
+            wrow[pp] = __shfl(wgt_lane, 16 * ii + pp, 64);
+            if (pp >= g.parts) wrow[pp] = 0.f;
+        }
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                if (ii + 1 < 4) load_row(ii + 1, xv[(ii + 1) & 1]);
-                const int ar = 4 * w + ii;
+        for (int hf = 0; hf < HF; ++hf) {
+            float v[8];
 #pragma unroll
-                for (int hf = 0; hf < HF; ++hf) {
-                    float v[8];
-                    char *dst = S + ar * ROWB + (((hf * 64 + l) ^ row_swizzle(ar)) << 4);
-                    if (p0 == 0) {
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = 0.f;
-                    } else {                               // more than four parts: accumulate onto the fp16 row
-                        const h8 prev = *(const h8 *)dst;
+            for (int pp = 0; pp < kMaxParts; ++pp) {
+                if (pp >= g.parts) continue;
+                if (wrow[pp] != 0.f) {                   // an empty part's row was never written
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = (float)prev[e];
-                    }
-#pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) {
-                        if (p0 + pp < g.parts) {
-                            const float wp = __shfl(wgt_lane, 16 * ii + p0 + pp, 64);
-                            if (wp != 0.f) {                   // an empty part's row was never written
-#pragma unroll
-                                for (int e = 0; e < 8; ++e) v[e] = fmaf(wp, (float)xv[ii & 1][hf][pp][e], v[e]);
-                            }
-                        }
-                    }
-                    h8 hv;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
-                    *(h8 *)dst = hv;
+                    for (int e = 0; e < 8; ++e) v[e] = fmaf(wrow[pp], (float)xv[ii][hf][pp][e], v[e]);
                 }
             }
+            h8 hv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
+            *(h8 *)(S + ar * ROWB + (((hf * 64 + l) ^ row_swizzle(ar)) << 4)) = hv;
         }
     }
 
@@ -466,6 +493,62 @@ static hipError_t launch_gemm(const GemmArgs &g, bool bf, int batches, hipStream
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// a2, query expansion (Eq. 9's Q_i (W_i^K)^T): ELQ[b, i*x + j, :] = Qp[b*x + j, head i] . (W_i^K)^T with
+// d_k = 64.  One workgroup owns 64 output columns of one head for up to 256 logical rows: its slice
+// of W^K (64 x 64, 8 KB) is read once and stays in registers as MFMA fragments while the four
+// wavefronts walk over the row tiles, so W^K is read once per 256 rows instead of once per 16.
+// Weights are the MFMA's A operand: a lane ends up with four consecutive columns of one row; the
+// 16 x 64 tile then goes through LDS and leaves as whole 128-byte lines.
+__global__ void __launch_bounds__(256)
+k_elq_slab(const GemmArgs g)
+{
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    constexpr int MT = 4;                               // row tiles per wavefront
+    __shared__ __attribute__((aligned(16))) _Float16 Ct[4][MT][16 * 72];   // rows 144 bytes apart
+
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r16 = l & 15, q4 = l >> 4;
+    const int n0 = blockIdx.x * 64, head = blockIdx.y;
+    const int mt0 = blockIdx.z * (4 * MT);              // first 16-row tile of this workgroup
+
+    u4 bfr[4][2], afr[MT][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            bfr[t][u] = *(const u4 *)((const f16_t *)g.Bt + (size_t)(n0 + 16 * t + r16) * g.ldb + head * 64 + 32 * u + 8 * q4);
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+        const int m = min((mt0 + w + 4 * mi) * 16 + r16, g.M - 1);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            afr[mi][u] = *(const u4 *)((const f16_t *)g.A + (size_t)m * g.lda + head * 64 + 32 * u + 8 * q4);
+    }
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, bfr[t][u]), __builtin_bit_cast(h8, afr[mi][u]), acc, 0, 0, 0);
+            *(h4 *)(&Ct[w][mi][r16 * 72 + 16 * t + 4 * q4]) = h4{(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
+        }
+    }
+    // a wavefront reads back only what it wrote: no barrier.  Eight lanes write one 128-byte row piece.
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            const int row = 8 * hf + (l >> 3), m = (mt0 + w + 4 * mi) * 16 + row;
+            if (m >= g.M) continue;
+            const size_t c_row = (size_t)(m / g.x) * g.c_rB + (size_t)(m % g.x) + (size_t)head * g.x;
+            *(h8 *)((f16_t *)g.C + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const h8 *)(&Ct[w][mi][row * 72 + 8 * (l & 7)]);
+        }
+    }
+}
+
 bool gemm_mfma_supported(int dtype, int d_m, int d_k)
 {
     return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024) && d_k == 64;
@@ -505,15 +588,16 @@ hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Works
     g.a_rB = p.beam; g.a_rJ = 1; g.a_col_z = p.d_k;
     g.bt_col_z = p.d_k;
     g.c_rB = Rs; g.c_rJ = 1; g.c_rI = p.beam;
-    return launch_gemm<A_STORAGE, C_F16, 8, 4, 1, 2>(g, false, p.heads, s);
+    hipLaunchKernelGGL(k_elq_slab, dim3(p.d_m / 64, p.heads, (g.M + 255) / 256), dim3(256), 0, s, g);
+    return hipGetLastError();
 }
 
 // merge + a6: A[b*beam+j, head i] = (sum_p w_p Xp[b,p,i*beam+j,:]) . W_i^V       fp16   (d_k = 64)
-hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rs,
+hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl,
                              hipStream_t s)
 {
     GemmArgs g = base_args(p);
-    g.A = ws.Xp; g.Bt = ctx->w.WvT; g.C = ws.A; g.ML = ws.ML; g.parts = parts; g.Rs = Rs;
+    g.A = ws.Xp; g.Bt = ctx->w.WvT; g.C = ws.A; g.ML = ws.ML; g.parts = pl.parts; g.Rs = pl.Rs;
     g.N = p.d_k; g.K = p.d_m; g.lda = p.d_m; g.ldb = p.d_m; g.ldc = p.hd;
     const dim3 grid((g.M + 15) / 16, p.heads), block(256);
     if (p.d_m == 1024) hipLaunchKernelGGL((k_vproj_slab<1024>), grid, block, 0, s, g);
