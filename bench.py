@@ -142,11 +142,14 @@ def main():
     core_bytes = tm.core_algorithmic_bytes(sum_len, w.d_m, w.elem_bytes)
     step_bytes = tm.step_algorithmic_bytes(sum_len, w.B, w.beam, w.d_m, w.heads * w.d_k, w.elem_bytes, 4)
     achieved = core_bytes / (core_avg_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM bytes per launch of that kernel from the committed rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE,
+    # each scaled by what the same counter reads for a plain copy of known size); null if none is committed
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f)
+            traffic_detail = json.load(f)
+        traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
 
     line = {
         "metric": "decode-step queries/sec (B x beam)",
@@ -160,7 +163,7 @@ def main():
                    "n": w.n, "sum_len": sum_len, "h_buffers_rotated": nbuf, "mfma_path": layer.uses_mfma,
                    "splits": a.splits},
         "roofline": {"bound": "hbm", "kernel": "attention core (a3-a5)", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "bytes_per_launch": core_bytes, "avg_launch_us": core_avg_ms * 1e3,
                      "min_launch_us": float(np.min(core_ms)) * 1e3},
         "step": {"algorithmic_bytes": step_bytes, "event_ms_per_step": ev_ms_per_step,
