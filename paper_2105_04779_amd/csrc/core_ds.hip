@@ -7,12 +7,11 @@
 // is read from LDS exactly twice per workgroup (once per product), whatever the number of rows.
 //
 //   fetch      each 1 KB piece of a tile row goes straight from HBM into one of four LDS tile
-//              slots (global_load_lds, no registers in flight; three tiles are outstanding while
-//              one is being used).  Lane i of a piece fetches chunk i ^ swizzle(row): the tile
+//              slots (global_load_lds, no registers in flight; two tiles are outstanding while
+//              two are in use).  Lane i of a piece fetches chunk i ^ swizzle(row): the tile
 //              lands in the XOR-swizzled order that keeps both operand read patterns spread over
-//              all banks.  A wavefront converts exactly the rows it fetched (bf16 -> fp16, in
-//              place), so landing needs no cross-wave handshake; the conversion of tile k+1 is
-//              interleaved with the score MFMAs of tile k.
+//              all banks.  bf16 fragments are converted to fp16 in registers after each LDS read,
+//              behind the MFMAs, so a tile is never rewritten in LDS.
 //   scores     S^T[t, r] partial over the wave's columns: v_mfma_f32_16x16x32_f16,
 //              A = H rows (ds_read_b128), B = the wave's slice of ELQ (registers).
 //   exchange   the four partial score tiles meet in LDS; wavefront g < RG sums them for row
@@ -22,6 +21,9 @@
 //   weighted   X^T[d, r] += H^T[d, t] P^T[t, r]: v_mfma_f32_32x32x16_f16, A = H columns through the
 //   sum        transposing LDS read (ds_read_b64_tr_b16), B = P from LDS.  Each wavefront keeps
 //              its d_m/4 x rows fp32 accumulators in AccVGPRs for the whole range.
+//
+// The scores and the softmax of a tile run one tile ahead of its weighted sum: the softmax's dependent
+// chain rides between the MFMAs of the previous tile's weighted sum, and there are two barriers per tile.
 //
 // Scores arrive pre-multiplied by log2(e)/sqrt(d_k), so the softmax is an exp2 of a difference.
 // The partial result (one per key-range split) leaves normalised by its own sum, in fp16, through

@@ -4,7 +4,7 @@
 // (W^Q, W^V, W^O are stored transposed at prepare time for exactly this; W^K already has that shape).
 //
 //   a1  Qp    = (q . W^Q + b^Q) * scale   k_gemm_slab  A = queries (storage dtype), Bt = (W^Q)^T (storage dtype)
-//   a2  ELQ_i = Qp_i . (W_i^K)^T          k_gemm_nt    A = Qp (fp16),               Bt = W^K in fp16     per head
+//   a2  ELQ_i = Qp_i . (W_i^K)^T          k_elq_slab   A = Qp (fp16),               Bt = W^K in fp16     per head
 //   a6  A_i   = X_i . W_i^V               k_vproj_slab A = merge of split partials, Bt = (W^V)^T in fp16 per head
 //   a7  out   = A . W^O + c_out           k_gemm_slab  A = A (fp16),                Bt = (W^O)^T in fp16
 //
@@ -16,7 +16,8 @@
 // k_gemm_slab: a workgroup stages 32 rows of A and 32 rows of Bt over the whole K in LDS with 1 KB
 // LDS-DMA pieces (full cache lines, every byte fetched once per workgroup), then its four wavefronts
 // split K.  k_vproj_slab: the same with the A rows built in LDS from the key-range partials.
-// k_gemm_nt: operand fragments straight from global memory (a2: K = d_k is tiny).
+// k_elq_slab: the weight slice stays in registers, operand fragments come straight from global memory
+// (a2: K = d_k is tiny).
 #include "el_internal.h"
 
 namespace el {
@@ -26,7 +27,6 @@ typedef __bf16 b8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
-enum { A_STORAGE = 0 };
 enum { C_F32 = 0, C_F16 = 1, C_BF16 = 2 };
 
 struct GemmArgs {
@@ -39,9 +39,7 @@ struct GemmArgs {
     int M, N, K;          // per batch (head)
     int lda, ldb, ldc;    // row strides in elements
     int x;                // beam: logical row m = b*x + j
-    // physical row of logical row m in batch z:  (m / x) * rB + (m % x) * rJ + z * rI
-    int a_rB, a_rJ, a_rI, c_rB, c_rJ, c_rI;
-    int a_col_z, bt_row_z, bt_col_z, c_col_z;   // per-batch offsets (elements / rows)
+    int c_rB;             // k_elq_slab: output row of logical row m, head i = (m / x) * c_rB + i * x + m % x
     // k_vproj_slab: A points at the normalised fp16 split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
     const float *ML;
     int parts, Rs;
@@ -56,153 +54,6 @@ template <> struct Frag<true> {
     typedef b8 type;
     static __device__ __forceinline__ f4 mfma(b8 a, b8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
 };
-
-// One wavefront computes a 16 x (16*NT) tile over a K range.  A workgroup is KS x WM x WN wavefronts
-// (KS * WM * WN = 4): KS wavefronts split K for the same tile and add up through LDS -- these GEMMs
-// are a few MFLOP per tile and latency-bound, so the point is to have every load of a tile in
-// flight at once (U k-steps are fetched before the first MFMA of a round).
-template <bool BF, int AK, int CK, int NT, int WN, int KS, int U>
-__global__ void __launch_bounds__(256)
-k_gemm_nt(const GemmArgs g)
-{
-    typedef typename Frag<BF>::type frag_t;
-    constexpr int WM = 4 / (WN * KS);
-    static_assert(WM >= 1 && WM * WN * KS == 4, "four wavefronts per workgroup");
-    __shared__ float red[KS > 1 ? (KS - 1) * WM * WN * NT * 256 : 1];
-
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int r16 = l & 15, q4 = l >> 4;
-    const int z = blockIdx.z;
-    const int ks = w % KS, wt = w / KS;              // K slice, tile slot inside the workgroup
-    const int m0 = (blockIdx.y * WM + wt / WN) * 16;
-    const int n0 = (blockIdx.x * WN + wt % WN) * 16 * NT;
-    const bool live = m0 < g.M && n0 < g.N;          // dead slots still reach the barrier below
-
-    // A row of this lane (clamped: lanes past M recompute the last row and never store)
-    const int m = min(m0 + r16, g.M - 1);
-    const size_t a_row = (size_t)(m / g.x) * g.a_rB + (size_t)(m % g.x) * g.a_rJ + (size_t)z * g.a_rI;
-
-    const char *Bt = (const char *)g.Bt;
-    size_t bt_off[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int n = min(n0 + 16 * t + r16, g.N - 1);
-        bt_off[t] = ((size_t)(g.bt_row_z * z + n) * g.ldb + (size_t)g.bt_col_z * z + 8 * q4) * 2;
-    }
-
-    f4 acc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
-
-    const int kspan = g.K / KS;                       // K is a multiple of 32 * KS (checked by the host)
-    const int kbeg = ks * kspan, kend = kbeg + kspan;
-
-    if (live)
-    for (int kr = kbeg; kr < kend; kr += 32 * U) {
-        // ---- fetch U k-steps of A and Bt fragments ----
-        u4 a_raw[U];
-        u4 b_raw[U][NT];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int k0 = kr + 32 * u;                    // the K slice is a multiple of 32 * U (chosen by the host)
-            a_raw[u] = *(const u4 *)((const char *)g.A + (a_row * g.lda + (size_t)g.a_col_z * z + k0 + 8 * q4) * 2);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) b_raw[u][t] = *(const u4 *)(Bt + bt_off[t] + (size_t)k0 * 2);
-        }
-        __builtin_amdgcn_sched_barrier(0);            // every fetch of the round is issued before the first MFMA
-        // ---- multiply ----
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const frag_t a_fr = __builtin_bit_cast(frag_t, a_raw[u]);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const frag_t bf = __builtin_bit_cast(frag_t, b_raw[u][t]);
-                // weights as the MFMA's A operand: the result tile is C^T, so a lane ends up with four
-                // consecutive output columns of one row and stores them as one vector
-                acc[t] = Frag<BF>::mfma(bf, a_fr, acc[t]);
-            }
-        }
-    }
-
-    // ---- add the K slices of a tile (slice 0 collects) ----
-    if (KS > 1) {
-        if (ks > 0) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                *(f4 *)(red + ((((ks - 1) * (WM * WN) + wt) * NT + t) * 64 + l) * 4) = acc[t];
-        }
-        __syncthreads();
-        if (ks > 0) return;
-#pragma unroll
-        for (int s = 1; s < KS; ++s)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const f4 o = *(const f4 *)(red + ((((s - 1) * (WM * WN) + wt) * NT + t) * 64 + l) * 4);
-                acc[t][0] += o[0]; acc[t][1] += o[1]; acc[t][2] += o[2]; acc[t][3] += o[3];
-            }
-    }
-    // One tile row per workgroup (WM == 1, no K split, fp16 out, no bias): the 16 x (64 NT WN) tile goes
-    // through LDS so that every store instruction writes whole 1 KB runs of one output row instead
-    // of 32-byte pieces of sixteen rows.
-    if constexpr (KS == 1 && WM == 1 && CK == C_F16) {
-        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-        constexpr int TW = 16 * NT * WN;                  // tile width in columns
-        static_assert(TW % 512 == 0, "rows are written in 1 KB runs");
-        __shared__ __attribute__((aligned(16))) _Float16 Ct[16 * (TW + 8)];   // +8: rows start 16 bytes apart in the banks
-        if (live) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int col = (wt % WN) * 16 * NT + 16 * t + 4 * q4;
-                *(h4 *)(Ct + r16 * (TW + 8) + col) = h4{(_Float16)(acc[t][0] * g.scale), (_Float16)(acc[t][1] * g.scale),
-                                                          (_Float16)(acc[t][2] * g.scale), (_Float16)(acc[t][3] * g.scale)};
-            }
-        }
-        __syncthreads();
-        const int nb0 = blockIdx.x * TW;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 4 * w + i, mm = blockIdx.y * 16 + row;
-            if (mm >= g.M) continue;
-            const size_t c_row = (size_t)(mm / g.x) * g.c_rB + (size_t)(mm % g.x) * g.c_rJ + (size_t)z * g.c_rI;
-#pragma unroll
-            for (int hf = 0; hf < TW / 512; ++hf) {
-                const int col = hf * 512 + 8 * l;
-                if (nb0 + col >= g.N) continue;          // N is a multiple of 8 on this path (checked by the host)
-                *(h8 *)((f16_t *)g.C + c_row * g.ldc + (size_t)g.c_col_z * z + nb0 + col) = *(const h8 *)(Ct + row * (TW + 8) + col);
-            }
-        }
-        return;
-    }
-    if (!live) return;
-
-    // C^T layout of the MFMA: this lane holds output row m0 + l%16, columns n0 + 16t + 4*q4 + j (j = 0..3)
-    const int mm = m0 + r16;
-    if (mm >= g.M) return;
-    const size_t c_row = (size_t)(mm / g.x) * g.c_rB + (size_t)(mm % g.x) * g.c_rJ + (size_t)z * g.c_rI;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int n = n0 + 16 * t + 4 * q4;
-        if (n >= g.N) continue;                       // N is a multiple of 4 (checked by the host)
-        float val[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float badd = 0.f;
-            if (g.bias) badd = BF ? to_f32(((const bf16_t *)g.bias)[g.c_col_z * z + n + j]) : to_f32(((const f16_t *)g.bias)[g.c_col_z * z + n + j]);
-            if (g.bias32) badd += g.bias32[g.c_col_z * z + n + j];
-            val[j] = (acc[t][j] + badd) * g.scale;
-        }
-        const size_t ci = c_row * g.ldc + (size_t)g.c_col_z * z + n;
-        if (CK == C_F32) {
-            *(f4 *)((float *)g.C + ci) = f4{val[0], val[1], val[2], val[3]};
-        } else if (CK == C_F16) {
-            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-            *(h4 *)((f16_t *)g.C + ci) = h4{(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) from_f32(val[j], (bf16_t *)g.C + ci + j);
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // Slab GEMM: C[M, N] = A[M, K] . Bt[N, K]^T for K = 512 or 1024 (rows of 1 or 2 KB).  One workgroup
@@ -483,16 +334,6 @@ hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hi
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int AK, int CK, int NT, int WN, int KS, int U>
-static hipError_t launch_gemm(const GemmArgs &g, bool bf, int batches, hipStream_t s)
-{
-    constexpr int WM = 4 / (WN * KS);
-    const dim3 grid((g.N + 16 * NT * WN - 1) / (16 * NT * WN), (g.M + 16 * WM - 1) / (16 * WM), batches), block(256);
-    if (bf) hipLaunchKernelGGL((k_gemm_nt<true, AK, CK, NT, WN, KS, U>), grid, block, 0, s, g);
-    else hipLaunchKernelGGL((k_gemm_nt<false, AK, CK, NT, WN, KS, U>), grid, block, 0, s, g);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------------------------
 // a2, query expansion (Eq. 9's Q_i (W_i^K)^T): ELQ[b, i*x + j, :] = Qp[b*x + j, head i] . (W_i^K)^T with
 // d_k = 64.  One workgroup owns 64 output columns of one head for up to 256 logical rows: its slice
@@ -585,9 +426,7 @@ hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Works
     GemmArgs g = base_args(p);
     g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ;
     g.N = p.d_m; g.K = p.d_k; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
-    g.a_rB = p.beam; g.a_rJ = 1; g.a_col_z = p.d_k;
-    g.bt_col_z = p.d_k;
-    g.c_rB = Rs; g.c_rJ = 1; g.c_rI = p.beam;
+    g.c_rB = Rs;
     hipLaunchKernelGGL(k_elq_slab, dim3(p.d_m / 64, p.heads, (g.M + 255) / 256), dim3(256), 0, s, g);
     return hipGetLastError();
 }
