@@ -154,8 +154,22 @@ k_core_ds(const CoreArgs a)
         else dma_piece(dst, voff, sbase);
     };
     auto issue_dma = [&](int kt, int slot) {
+        if (kt < k1 && (kt + 1) * kTileRows16 <= len) {
+            // the common case, a whole tile inside the range: one source base and four destinations,
+            // without the per-row selects below
+            const char *sbase = Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB;
+            const unsigned dst0 = t_lds + slot * SLOT + (4 * w) * ROWB;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) issue_dma_row(kt, slot, i);
+            for (int i = 0; i < 4; ++i) {
+                const int f = (i << 2) | w;
+                const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
+                if (PIECES == 2) dma_row_2k(dst0 + i * ROWB, voff, sbase);
+                else dma_piece(dst0 + i * ROWB, voff, sbase);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) issue_dma_row(kt, slot, i);
+        }
     };
     // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
     auto wait_own = [&](int later_tiles) {
