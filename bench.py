@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--splits", type=int, default=0, help="key-range splits (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
     ap.add_argument("--same-h", action="store_true", help="reuse one H buffer every step (cache-warm; not the reported protocol)")
+    ap.add_argument("--layers", type=int, default=1, help="attention layers (own weights each) that read the same H in one step")
+    ap.add_argument("--sweep", choices=["n", "beam"], default=None,
+                    help="one line per point: input length 64..1024 at beam 4, or beam 1..8 at length 1024 (BART-large widths, B 64)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run a plain device copy of known size (1 GiB read + 1 GiB written per launch, 10 launches): "
                          "what FETCH_SIZE / WRITE_SIZE read for it scales the counters of the real run")
@@ -98,17 +101,45 @@ def main():
         print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": src.numel() * 4,
                           "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
         return
+    # ---- extra modes (rows after the contract's: sweeps of input length and beam size, several layers
+    #      reading one H); each prints one line per point, without the CPU baseline ----
+    if a.sweep:
+        base = wl.WORKLOADS["c3_bart_large_bf16"]
+        if a.sweep == "n":        # beam 4, every input of length n (section 4.1.2's first sweep)
+            points = [wl.custom(f"sweep_n{n}", dtype=base.dtype, B=base.B, beam=4, heads=base.heads, d_m=base.d_m,
+                                d_k=base.d_k, n=n, index=200 + k) for k, n in enumerate((64, 128, 256, 512, 1024))]
+        else:                     # n = 1024, beam 1..8 (its second sweep)
+            points = [wl.custom(f"sweep_beam{x}", dtype=base.dtype, B=base.B, beam=x, heads=base.heads, d_m=base.d_m,
+                                d_k=base.d_k, n=1024, index=210 + k) for k, x in enumerate((1, 2, 4, 6, 8))]
+        for w in points:
+            print(json.dumps(measure(a, w, torch, np, el_attn, tm, wl)), flush=True)
+        return
     w = wl.WORKLOADS[a.workload]
+    line = measure(a, w, torch, np, el_attn, tm, wl)
+    if a.cpu_seconds > 0 and a.layers == 1:
+        line["cpu_baseline"] = cpu_baseline(w, wl, a.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+def measure(a, w, torch, np, el_attn, tm, wl):
+    """One bench line for workload `w`: whole-step throughput, then the core kernel timed by itself."""
+    from dataclasses import replace
     td = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
 
     # ---- inputs, resident in HBM before anything is timed -----------------------------------
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from helpers import device_weights
-    W = wl.weights(w)
-    layer = el_attn.ElAttention(device_weights(W, w.dtype), heads=w.heads, d_k=w.d_k, dtype=w.dtype,
-                                max_batch=w.B, max_beam=w.beam, max_n=w.n)
+    # `--layers L`: L attention layers with their own weights read the same H in every step (what the L
+    # decoder layers of one model do with one encoder output); layer 0 has the workload's own weights
+    layers = []
+    for k in range(a.layers):
+        W = wl.weights(w if k == 0 else replace(w, index=w.index + 1000 * k))
+        layers.append(el_attn.ElAttention(device_weights(W, w.dtype), heads=w.heads, d_k=w.d_k, dtype=w.dtype,
+                                          max_batch=w.B, max_beam=w.beam, max_n=w.n))
+    layer = layers[0]
     if a.splits:
-        layer.set_splits(a.splits)
+        for ly in layers:
+            ly.set_splits(a.splits)
     lens = wl.lengths(w)
     Ld = torch.from_numpy(lens).cuda()
     h_bytes = w.B * w.n * w.d_m * w.elem_bytes
@@ -121,7 +152,9 @@ def main():
 
     def run(steps, start=0):
         for i in range(steps):
-            layer.decode_step(Hs[(start + i) % nbuf], Ld, Q, out=out)
+            H = Hs[(start + i) % nbuf]
+            for ly in layers:
+                ly.decode_step(H, Ld, Q, out=out)
 
     # ---- whole-step throughput -------------------------------------------------------------
     run(a.warmup)
@@ -138,12 +171,14 @@ def main():
     assert torch.isfinite(out).all()
 
     # ---- the dominant kernel (attention core) timed by itself, HIP events on its own stream ----
+    # (with several layers: the last layer's, i.e. the one that finds H already touched in this step)
     core_steps = min(a.steps, 1000)
-    layer.core_timing(core_steps)
+    timed = layers[-1]
+    timed.core_timing(core_steps)
     run(core_steps, a.warmup + a.steps)
     torch.cuda.synchronize()
-    core_ms = layer.read_core_timing(core_steps)
-    layer.core_timing(0)
+    core_ms = timed.read_core_timing(core_steps)
+    timed.core_timing(0)
     core_avg_ms = float(np.mean(core_ms))
 
     sum_len = int(lens.sum())
@@ -154,14 +189,15 @@ def main():
     # each scaled by what the same counter reads for a plain copy of known size); null if none is committed
     traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and a.layers == 1:
         with open(tpath) as f:
             traffic_detail = json.load(f)
         traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
 
+    L = a.layers
     line = {
-        "metric": "decode-step queries/sec (B x beam)",
-        "value": w.B * w.beam / (ms_per_step * 1e-3),
+        "metric": "decode-step queries/sec (B x beam)" + ("" if L == 1 else f", {L} layers on one H, a query counted once per layer"),
+        "value": w.B * w.beam * L / (ms_per_step * 1e-3),
         "unit": "queries/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step,
@@ -169,19 +205,19 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "beam": w.beam, "heads": w.heads, "d_m": w.d_m, "d_k": w.d_k,
                    "n": w.n, "sum_len": sum_len, "h_buffers_rotated": nbuf, "mfma_path": layer.uses_mfma,
-                   "splits": a.splits},
+                   "splits": a.splits, "layers": L},
         "roofline": {"bound": "hbm", "kernel": "attention core (a3-a5)", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "bytes_per_launch": core_bytes, "avg_launch_us": core_avg_ms * 1e3,
                      "min_launch_us": float(np.min(core_ms)) * 1e3},
-        "step": {"algorithmic_bytes": step_bytes, "event_ms_per_step": ev_ms_per_step,
+        "step": {"algorithmic_bytes": step_bytes, "event_ms_per_step": ev_ms_per_step, "ms_per_layer": ms_per_step / L,
                  "hbm_frac_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                 "flops": tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k),
-                 "tflops": tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k) / (ms_per_step * 1e-3) / 1e12},
+                 "flops": L * tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k),
+                 "tflops": L * tm.step_flops(sum_len, w.B, w.beam, w.heads, w.d_m, w.d_k) / (ms_per_step * 1e-3) / 1e12},
     }
-    if a.cpu_seconds > 0:
-        line["cpu_baseline"] = cpu_baseline(w, wl, a.cpu_seconds)
-    print(json.dumps(line), flush=True)
+    for ly in layers:
+        ly.close()
+    return line
 
 
 if __name__ == "__main__":

@@ -182,6 +182,26 @@ def test_expand_query_matches_eq5():
     assert rel_err(elq, ref) <= 1e-5
 
 
+# ---- several layers, one H ------------------------------------------------------------------------------------
+def test_layers_with_own_weights_share_one_H():
+    """Section 3.3 / Figure 1: every decoder layer reads the same encoder output; contexts do not interfere."""
+    from dataclasses import replace
+    import torch
+    w = wl.custom("layers", dtype="bf16", B=3, beam=4, heads=16, d_m=1024, d_k=64, n=180, len_lo=40, len_hi=180, index=62)
+    H, Q, L = wl.batch(w, poison=True)
+    Hd, Qd = to_device(H, w.dtype), to_device(Q, w.dtype)
+    Ld = torch.from_numpy(L).cuda()
+    Ws = [wl.weights(w if k == 0 else replace(w, index=w.index + 1000 * k)) for k in range(3)]
+    layers = [make_layer(w, W) for W in Ws]
+    outs = [ly.decode_step(Hd, Ld, Qd) for ly in layers]          # all queued on one stream before any is checked
+    torch.cuda.synchronize()
+    for k, (W, y) in enumerate(zip(Ws, outs)):
+        err = rel_err(y.float().cpu().numpy(), oracle_out(w, W, H, Q, L))
+        record(f"layers: layer {k} err={err:.3e}")
+        assert err <= TOL[w.dtype]
+    assert rel_err(outs[1].float().cpu().numpy(), outs[0].float().cpu().numpy()) > 0.1   # different weights, different results
+
+
 # ---- argument validation with a live context ---------------------------------------------------------------
 def test_decode_step_argument_errors():
     import ctypes
