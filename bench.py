@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
     ap.add_argument("--same-h", action="store_true", help="reuse one H buffer every step (cache-warm; not the reported protocol)")
     ap.add_argument("--layers", type=int, default=1, help="attention layers (own weights each) that read the same H in one step")
+    ap.add_argument("--gather", action="store_true",
+                    help="state maintenance instead of the decode step: re-order 512 per-beam histories of up to 1024 rows "
+                         "(GPT-2-medium widths) by parent beam; one line with the bytes moved per second")
     ap.add_argument("--sweep", choices=["n", "beam"], default=None,
                     help="one line per point: input length 64..1024 at beam 4, or beam 1..8 at length 1024 (BART-large widths, B 64)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -101,6 +104,9 @@ def main():
         print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": src.numel() * 4,
                           "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
         return
+    if a.gather:
+        print(json.dumps(measure_gather(a, torch, np, el_attn, wl)), flush=True)
+        return
     # ---- extra modes (rows after the contract's: sweeps of input length and beam size, several layers
     #      reading one H); each prints one line per point, without the CPU baseline ----
     if a.sweep:
@@ -119,6 +125,41 @@ def main():
     if a.cpu_seconds > 0 and a.layers == 1:
         line["cpu_baseline"] = cpu_baseline(w, wl, a.cpu_seconds)
     print(json.dumps(line), flush=True)
+
+
+def measure_gather(a, torch, np, el_attn, wl):
+    """Beam re-order of per-beam histories (section 3.1.1's state for self-attention): every new beam copies the
+    valid rows of its parent's H.  Bytes moved = valid rows read once + written once; bound: HBM."""
+    w = wl.WORKLOADS["c5_gpt2_medium_n1024_bf16"]
+    B, n, d_m = w.B, w.n, w.d_m
+    g = torch.Generator(device="cuda").manual_seed(wl.BASE_SEED + 300)
+    src = torch.randn((B, n, d_m), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    dst = torch.empty_like(src)
+    rng = np.random.default_rng(wl.BASE_SEED + 301)
+    lens = rng.integers(n // 2, n, size=B, endpoint=True).astype(np.int32)
+    index = (np.arange(B) // 4 * 4 + rng.integers(0, 4, size=B)).astype(np.int32)   # a parent among the 4 beams of the same sentence
+    Ld, Idx = torch.from_numpy(lens).cuda(), torch.from_numpy(index).cuda()
+    out_lens = torch.empty((B,), dtype=torch.int32, device="cuda")
+    for _ in range(a.warmup):
+        el_attn.gather_batch(src, Ld, Idx, H_dst=dst, lengths_dst=out_lens)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        el_attn.gather_batch(src, Ld, Idx, H_dst=dst, lengths_dst=out_lens)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    moved = 2 * int(lens[index].sum()) * d_m * 2
+    gbs = moved / (ms * 1e-3) / 1e9
+    return {"metric": "state gather, bytes read + written per second", "value": gbs, "unit": "GB/s", "n_gpus": 1,
+            "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "beam re-order of per-beam histories, GPT-2-medium widths", "B": B, "n": n, "d_m": d_m,
+                       "sum_len": int(lens[index].sum()), "event_ms_per_step": e0.elapsed_time(e1) / a.steps},
+            "roofline": {"bound": "hbm", "kernel": "k_gather_batch", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": moved, "avg_launch_us": ms * 1e3}}
 
 
 def measure(a, w, torch, np, el_attn, tm, wl):

@@ -179,6 +179,37 @@ int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);
 el_status el_attn_core_timing_enable(el_attn_ctx *ctx, int32_t max_steps);
 el_status el_attn_core_timing_read(el_attn_ctx *ctx, float *ms_out, int32_t capacity, int32_t *count);
 
+/*
+ * State maintenance between decode steps (section 3.1.1 and the "reorder" cost the paper's
+ * Algorithm 3 leaves to the caller): the state of EL-attention is the hidden states themselves,
+ * so keeping it in step with the search is a gather of whole batch elements,
+ *
+ *     H_dst[i, 0:len, :] = H_src[index[i], 0:len, :],   len = lengths_src[index[i]],
+ *     lengths_dst[i]     = len                                     for i < B_dst.
+ *
+ * With index = the batch elements that are still running it drops finished sentences
+ * (encoder-decoder attention: one H per sentence, shared by its beams); with index = the parent
+ * beam of every surviving beam it re-orders per-beam histories after a beam-search step
+ * (self-attention, B := B*beam).  Only the valid prefix is read and written: rows at or beyond
+ * len keep whatever H_dst held.
+ *
+ *   H_src     [B_src, n, d_model], row stride d_model, batch stride src_batch_stride ELEMENTS, device
+ *   H_dst     [B_dst, n, d_model], batch stride dst_batch_stride ELEMENTS, device; must not overlap H_src
+ *   lengths_src [B_src] int32 device or NULL (every element has length n)
+ *   lengths_dst [B_dst] int32 device or NULL (not written)
+ *   index     [B_dst] int32 device; an entry outside [0, B_src) leaves its destination untouched
+ *             (and its lengths_dst entry at 0)
+ *   dtype     element type of H (EL_F32, EL_F16, EL_BF16); d_model * element size must be a multiple of 16 bytes
+ *
+ * Asynchronous on `stream`, allocates nothing, needs no context.
+ * Errors: INVALID_ARG (null H_src/H_dst/index, sizes < 1, strides < n*d_model, bad dtype, row bytes
+ * not a multiple of 16, H pointers not 16-byte aligned), HIP (launch failure).
+ */
+el_status el_attn_gather_batch(el_dtype dtype, int32_t d_model,
+                               const void *H_src, int64_t src_batch_stride, const int32_t *lengths_src, int32_t B_src,
+                               void *H_dst, int64_t dst_batch_stride, int32_t *lengths_dst, int32_t B_dst,
+                               const int32_t *index, int32_t n, void *stream);
+
 /* Release the context and its packed weights (not the workspace, which the caller owns). */
 el_status el_attn_destroy(el_attn_ctx *ctx);
 

@@ -9,6 +9,8 @@ module compiles it with gcc on first use and marshals numpy arrays to it.
 ``mha_reference``  multi-head attention by its definition (Eq. 1, Eq. 2/6).
 ``el_reference``   the same quantity in the evaluation order of Eq. 9; used by
                    the tests to check the losslessness identity on the oracle.
+``gather_batch_reference``  the state gather between decode steps (section 3.1.1's
+                   state, re-ordered / compacted by the search), by its definition.
 """
 from __future__ import annotations
 
@@ -117,3 +119,26 @@ def mha_reference(H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, *, heads,
 def el_reference(H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, *, heads, d_k):
     """Eq. 9: the expanded-query evaluation order, in float64 (oracle self-check only)."""
     return _call("el_oracle", H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, Wo, bo, heads, d_k)
+
+
+def gather_batch_reference(H_src, lengths_src, index, H_dst_before):
+    """State maintenance by its definition, one row at a time (section 3.1.1: the state is H itself).
+
+    H_dst[i, t, :] = H_src[index[i], t, :] for t < lengths_src[index[i]]; other rows keep what
+    ``H_dst_before`` held; lengths_dst[i] = lengths_src[index[i]].  An index outside [0, B_src)
+    leaves its destination untouched and reports length 0.  Arrays are copied bit for bit
+    (any dtype); returns (H_dst, lengths_dst).
+    """
+    H_src = np.asarray(H_src)
+    out = np.array(H_dst_before, copy=True)
+    n = H_src.shape[1]
+    lens = np.full(H_src.shape[0], n, dtype=np.int32) if lengths_src is None else np.asarray(lengths_src, dtype=np.int32)
+    new_lens = np.zeros(len(index), dtype=np.int32)
+    for i, src in enumerate(index):
+        src = int(src)
+        if src < 0 or src >= H_src.shape[0]:
+            continue
+        new_lens[i] = lens[src]
+        for t in range(int(lens[src])):
+            out[i, t, :] = H_src[src, t, :]
+    return out, new_lens

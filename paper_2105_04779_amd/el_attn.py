@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
     "el_attn_uses_mfma",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
+    "el_attn_gather_batch",
     "el_attn_destroy", "el_attn_status_string", "el_attn_version",
 )
 
@@ -71,6 +72,8 @@ def _load():
     lib.el_attn_core_timing_enable.restype = ctypes.c_int
     lib.el_attn_core_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
     lib.el_attn_core_timing_read.restype = ctypes.c_int
+    lib.el_attn_gather_batch.argtypes = [ctypes.c_int, i32, vp, i64, vp, i32, vp, i64, vp, i32, vp, i32, vp]
+    lib.el_attn_gather_batch.restype = ctypes.c_int
     lib.el_attn_destroy.argtypes = [vp]
     lib.el_attn_destroy.restype = ctypes.c_int
     lib.el_attn_status_string.argtypes = [ctypes.c_int]
@@ -134,6 +137,12 @@ def el_attn_uses_mfma(ctx) -> int:
     return int(lib.el_attn_uses_mfma(ctx))
 
 
+def el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B_src,
+                         H_dst, dst_batch_stride, lengths_dst, B_dst, index, n, stream=None) -> int:
+    return lib.el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B_src,
+                                    H_dst, dst_batch_stride, lengths_dst, B_dst, index, n, stream)
+
+
 def el_attn_core_timing_enable(ctx, max_steps) -> int:
     return lib.el_attn_core_timing_enable(ctx, max_steps)
 
@@ -163,6 +172,32 @@ def _ptr(t):
 def _stream_handle():
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def gather_batch(H_src, lengths_src, index, *, H_dst=None, lengths_dst=None):
+    """H_dst[i, :len] = H_src[index[i], :len], lengths_dst[i] = len (marshalling only; see el_attn_gather_batch).
+
+    H_src [B_src, n, d_m] device tensor (last two dimensions contiguous), lengths_src int32 [B_src] or None,
+    index int32 [B_dst] device tensor.  Returns (H_dst, lengths_dst); fresh destination rows beyond a length
+    are left as allocated.
+    """
+    import torch
+    if H_src.dim() != 3 or H_src.stride(2) != 1 or H_src.stride(1) != H_src.shape[2]:
+        raise ValueError("H_src must be [B, n, d_m] with contiguous rows")
+    code = {torch.float32: EL_F32, torch.float16: EL_F16, torch.bfloat16: EL_BF16}[H_src.dtype]
+    B_src, n, d_m = H_src.shape
+    B_dst = int(index.shape[0])
+    if index.dtype != torch.int32 or not index.is_cuda:
+        raise ValueError("index must be an int32 device tensor")
+    if H_dst is None:
+        H_dst = torch.empty((B_dst, n, d_m), dtype=H_src.dtype, device=H_src.device)
+    if lengths_dst is None and lengths_src is not None:
+        lengths_dst = torch.empty((B_dst,), dtype=torch.int32, device=H_src.device)
+    st = el_attn_gather_batch(code, d_m, _ptr(H_src), H_src.stride(0), _ptr(lengths_src), B_src,
+                              _ptr(H_dst), H_dst.stride(0), _ptr(lengths_dst), B_dst, _ptr(index), n, _stream_handle())
+    if st != EL_OK:
+        raise ElAttnError(st, "el_attn_gather_batch")
+    return H_dst, lengths_dst
 
 
 class ElAttention:

@@ -82,3 +82,22 @@ def test_prepare_without_a_device_reports_hip_error(ea):
     st, ctx = ea.el_attn_prepare(_cfg(ea), FAKE, None, FAKE, None, FAKE, None, FAKE, None)
     assert st == ea.EL_ERR_HIP
     assert not ctx.value
+
+
+def test_gather_batch_rejects_bad_arguments_before_any_device_work(ea):
+    I = ea.EL_ERR_INVALID_ARG
+    A, B, X = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000), ctypes.c_void_p(0x30000)   # never dereferenced
+
+    def call(dtype=ea.EL_BF16, d_model=1024, src=A, sstride=64 * 1024, lsrc=None, bsrc=4,
+             dst=B, dstride=64 * 1024, ldst=None, bdst=3, index=X, n=64):
+        return ea.el_attn_gather_batch(dtype, d_model, src, sstride, lsrc, bsrc, dst, dstride, ldst, bdst, index, n)
+
+    assert call(src=None) == I and call(dst=None) == I and call(index=None) == I
+    assert call(dtype=5) == I
+    for bad in (dict(d_model=0), dict(bsrc=0), dict(bdst=0), dict(n=0), dict(bdst=70000)):
+        assert call(**bad) == I, bad
+    assert call(sstride=64 * 1024 - 8) == I and call(dstride=100) == I          # shorter than n rows
+    assert call(d_model=1020) == I                                              # 2040-byte rows: not a multiple of 16
+    assert call(dtype=ea.EL_F32, d_model=6, sstride=6 * 64, dstride=6 * 64) == I
+    assert call(src=ctypes.c_void_p(0x10008)) == I                              # misaligned
+    assert call(sstride=64 * 1024 + 4) == I                                     # batch stride breaks the 16-byte alignment

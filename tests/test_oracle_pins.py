@@ -238,3 +238,23 @@ def test_rejects_bad_lengths():
 
 def test_thread_count_reported():
     assert oracle.num_threads() >= 1
+
+
+# ---- state gather: the loop-by-definition oracle against numpy's own indexing on a case where both apply ----
+def test_gather_reference_equals_fancy_indexing_on_full_lengths():
+    import oracle
+    rng = np.random.default_rng(5)
+    H = rng.standard_normal((5, 7, 8)).astype(np.float32)
+    idx = np.array([4, 0, 0, 3], dtype=np.int32)
+    before = np.full((4, 7, 8), -7.0, dtype=np.float32)
+    out, lens = oracle.gather_batch_reference(H, None, idx, before)
+    assert np.array_equal(out, H[idx]) and np.array_equal(lens, np.full(4, 7, dtype=np.int32))
+    # ragged: rows at or beyond the length keep the old contents, rows below it are the source's
+    L = np.array([7, 1, 3, 0, 5], dtype=np.int32)
+    out, lens = oracle.gather_batch_reference(H, L, idx, before)
+    assert np.array_equal(lens, L[idx])
+    for i, s in enumerate(idx):
+        assert np.array_equal(out[i, :L[s]], H[s, :L[s]]) and np.all(out[i, L[s]:] == -7.0)
+    # an index outside the source leaves its destination alone
+    out, lens = oracle.gather_batch_reference(H, L, np.array([9, -1, 2], dtype=np.int32), before[:3])
+    assert np.all(out[0] == -7.0) and np.all(out[1] == -7.0) and lens.tolist() == [0, 0, 3]
