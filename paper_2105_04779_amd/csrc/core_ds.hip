@@ -73,13 +73,8 @@ __device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
     return __builtin_bit_cast(h8, x);
 }
 
-#if defined(EL_CORE_PROF) && !defined(EL_CORE_TS)
-#define EL_PROF_DECL unsigned long long prof_t = clock64(), prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long prof_w0 = wall_clock64(), prof_c0 = prof_t;
-#define EL_PROF(i) { const unsigned long long now = clock64(); prof_acc[i] += now - prof_t; prof_t = now; }
-#else
-#define EL_PROF_DECL
-#define EL_PROF(i)
-#endif
+// Debug builds (-DEL_CORE_TS) stamp s_memtime at fixed points of the loop without waiting for it, and report the
+// per-phase cycle totals of workgroup 0, wavefront 0 through CoreArgs::prof.
 #ifdef EL_CORE_TS
 #define EL_TS_DECL unsigned long long ts[12], ts_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long ts_w0 = wall_clock64(), ts_c0 = clock64();
 #define EL_TS(i) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_memtime %0" : "=s"(ts[i])); __builtin_amdgcn_sched_barrier(0); }
@@ -190,7 +185,6 @@ k_core_ds(const CoreArgs a)
         }
     };
 
-    EL_PROF_DECL
     EL_TS_DECL
     // ---- prologue: request two tiles, wait for the first ----
     // the first two tiles are requested before anything else is: they take the longest to arrive
@@ -254,7 +248,6 @@ k_core_ds(const CoreArgs a)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  // ELQ and, requested before it, both tiles
     if (nloc > 0) zero_ragged(k0, 0);
     __syncthreads();
-    EL_PROF(0)
 
     // ---- scores of tile kk (slot kk&3) over this wavefront's columns, left in LDS for the exchange.
     //      The fetch of tile kk+2 is requested between the fragment loads and the first MFMA (it fills
@@ -443,31 +436,23 @@ k_core_ds(const CoreArgs a)
     //          at the start of the scores of tile j+1), and has waited for its own rows of tile j+1.
     if (nloc > 0) {
         scores(0);
-        EL_PROF(2)
         __syncthreads();                                              // B1(0)
-        EL_PROF(3)
         sm_load(); sm_stage1(k0); sm_stage2(); sm_stage3(); sm_stage4(0);
         wait_own(1);
         if (nloc > 1) zero_ragged(k0 + 1, 1);
-        EL_PROF(4)
         __syncthreads();                                              // B2(0)
-        EL_PROF(5)
         for (int kk = 1; kk < nloc; ++kk) {
             EL_TS(0)
             scores(kk);
             pv_loads(kk - 1);
-            EL_PROF(2)
             EL_TS(5)
             __syncthreads();                                          // B1(kk)
-            EL_PROF(3)
             EL_TS(6)
             pv(kk - 1, std::true_type{});
             wait_own(1);
             if (kk + 1 < nloc) zero_ragged(k0 + kk + 1, (kk + 1) & 3);
-            EL_PROF(6)
             EL_TS(9)
             __syncthreads();                                          // B2(kk)
-            EL_PROF(7)
             EL_TS(10)
 #ifdef EL_CORE_TS
             for (int i = 0; i < 10; ++i) ts_acc[i] += ts[i + 1] - ts[i];
@@ -475,7 +460,6 @@ k_core_ds(const CoreArgs a)
         }
         pv_loads(nloc - 1);
         pv(nloc - 1, std::false_type{});
-        EL_PROF(1)
     }
 
     // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
@@ -496,7 +480,6 @@ k_core_ds(const CoreArgs a)
         }
     }
     __syncthreads();
-    EL_PROF(9)
     if (nloc <= 0) return;                            // nothing accumulated: the merge skips sum == 0
 
     // stage [row][d] in fp16 over the tile slots (8-byte units XOR-swizzled by the row to spread the
@@ -518,7 +501,6 @@ k_core_ds(const CoreArgs a)
         }
     }
     __syncthreads();
-    EL_PROF(10)
     f16_t *x_out = a.Xp + (((size_t)b * parts + part) * a.Rs + row0) * DM;
     constexpr int ROWS_PER_WAVE = NB * 32 / 4;
 #pragma unroll
@@ -539,16 +521,6 @@ k_core_ds(const CoreArgs a)
         a.prof[12] = (unsigned long long)(nloc > 1 ? nloc - 1 : 1);
         a.prof[13] = wall_clock64() - ts_w0;
         a.prof[14] = clock64() - ts_c0;
-    }
-#endif
-#if defined(EL_CORE_PROF) && !defined(EL_CORE_TS)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    EL_PROF(11)
-    if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
-        for (int i = 0; i < 12; ++i) a.prof[i] = prof_acc[i];
-        a.prof[12] = (unsigned long long)nloc;
-        a.prof[13] = wall_clock64() - prof_w0;
-        a.prof[14] = clock64() - prof_c0;
     }
 #endif
 }
