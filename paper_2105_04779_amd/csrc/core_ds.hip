@@ -73,15 +73,6 @@ __device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
     return __builtin_bit_cast(h8, x);
 }
 
-// Debug builds (-DEL_CORE_TS) stamp s_memtime at fixed points of the loop without waiting for it, and report the
-// per-phase cycle totals of workgroup 0, wavefront 0 through CoreArgs::prof.
-#ifdef EL_CORE_TS
-#define EL_TS_DECL unsigned long long ts[12], ts_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; const unsigned long long ts_w0 = wall_clock64(), ts_c0 = clock64();
-#define EL_TS(i) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_memtime %0" : "=s"(ts[i])); __builtin_amdgcn_sched_barrier(0); }
-#else
-#define EL_TS_DECL
-#define EL_TS(i)
-#endif
 
 template <int DM, bool BF16_, int RG>
 __global__ void __launch_bounds__(256)
@@ -185,7 +176,6 @@ k_core_ds(const CoreArgs a)
         }
     };
 
-    EL_TS_DECL
     // ---- prologue: request two tiles, wait for the first ----
     // the first two tiles are requested before anything else is: they take the longest to arrive
     if (nloc > 0) {
@@ -258,9 +248,7 @@ k_core_ds(const CoreArgs a)
         u4 hb[KC];
 #pragma unroll
         for (int c = 0; c < KC; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c & 3] + (c >> 2) * 256);
-        EL_TS(1)
         issue_dma(k0 + kk + 2, (kk + 2) & 3);
-        EL_TS(2)
         f4 sc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) sc[rg] = f4{0.f, 0.f, 0.f, 0.f};
@@ -288,10 +276,8 @@ k_core_ds(const CoreArgs a)
             __builtin_amdgcn_sched_barrier(0);
             cur = nxt;
         }
-        EL_TS(3)
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) *(f4 *)(Sx + ((w * RG + rg) * 64 + l) * 4) = sc[rg];
-        EL_TS(4)
     };
 
     // ---- softmax bookkeeping of row group w for one tile, cut into stages that the weighted sum of the
@@ -383,7 +369,6 @@ k_core_ds(const CoreArgs a)
                 }
             }
         }
-        EL_TS(7)
         constexpr int S0 = MB >= 8 ? 1 : 0;                            // block after which softmax stage 1 runs
         auto packed = [&](int mb) {
             const s4 lo = tb[mb % PD][0], hi = tb[mb % PD][1];
@@ -425,7 +410,6 @@ k_core_ds(const CoreArgs a)
             }
             cur = nxt;
         }
-        EL_TS(8)
     };
 
     // Tile j's scores and softmax run one tile ahead of its weighted sum.  What crosses the barriers:
@@ -442,21 +426,13 @@ k_core_ds(const CoreArgs a)
         if (nloc > 1) zero_ragged(k0 + 1, 1);
         __syncthreads();                                              // B2(0)
         for (int kk = 1; kk < nloc; ++kk) {
-            EL_TS(0)
             scores(kk);
             pv_loads(kk - 1);
-            EL_TS(5)
             __syncthreads();                                          // B1(kk)
-            EL_TS(6)
             pv(kk - 1, std::true_type{});
             wait_own(1);
             if (kk + 1 < nloc) zero_ragged(k0 + kk + 1, (kk + 1) & 3);
-            EL_TS(9)
             __syncthreads();                                          // B2(kk)
-            EL_TS(10)
-#ifdef EL_CORE_TS
-            for (int i = 0; i < 10; ++i) ts_acc[i] += ts[i + 1] - ts[i];
-#endif
         }
         pv_loads(nloc - 1);
         pv(nloc - 1, std::false_type{});
@@ -515,14 +491,6 @@ k_core_ds(const CoreArgs a)
             *(h8 *)(x_out + (size_t)srow * DM + hf * 512 + 8 * l) = h8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
         }
     }
-#ifdef EL_CORE_TS
-    if (blockIdx.x == 0 && threadIdx.x == 0 && a.prof) {
-        for (int i = 0; i < 10; ++i) a.prof[i] = ts_acc[i];
-        a.prof[12] = (unsigned long long)(nloc > 1 ? nloc - 1 : 1);
-        a.prof[13] = wall_clock64() - ts_w0;
-        a.prof[14] = clock64() - ts_c0;
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -54,10 +54,6 @@ __global__ void k_merge_exp2(const f16_t *__restrict__ Xp, const float *__restri
     Xn[((size_t)b * R + r) * d_m + d] = num / den;
 }
 
-#ifdef EL_CORE_TS
-static unsigned long long *g_core_prof = nullptr;
-extern "C" void el_attn_debug_set_prof(unsigned long long *p) { g_core_prof = p; }
-#endif
 
 // ---------------------------------------------------------------------------------------------
 bool core_mfma_supported(int dtype, int d_m)
@@ -122,9 +118,6 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
     a.elq = (const f16_t *)ws.ELQ; a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
-#ifdef EL_CORE_TS
-    a.prof = g_core_prof;
-#endif
     const bool bf = p.dtype == EL_BF16;
     return launch_core_ds(a, p.d_m, bf, pl.nrg, s);
 }

@@ -123,9 +123,6 @@ struct CoreArgs {
     f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
     float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
     int n, B, R, Rs, S, nblocks;
-#ifdef EL_CORE_TS
-    unsigned long long *prof;   // per-phase cycle totals of workgroup 0, wave 0 (debug builds only)
-#endif
 };
 hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s);
 struct CorePlan {
