@@ -74,7 +74,9 @@ typedef struct {
  * Step a0 (once per attention layer, off the per-step path): take the layer's
  * projection weights, keep private packed copies, and fold the biases as the
  * closing remark of appendix B allows: c_out = b^O + sum_i b_i^V W_i^O (Eq. 8/9)
- * is computed here, and b^K is accepted but never read (it cancels, Eq. 7).
+ * is computed here.  b^K cancels inside one softmax (Eq. 7) and the decode step
+ * never reads it; only the segment form below, whose statistics are compared
+ * across key sets, keeps it.
  *
  *   Wq, Wk, Wv  [d_model, heads*d_k]   device, `dtype`
  *   Wo          [heads*d_k, d_model]   device, `dtype`
@@ -138,6 +140,56 @@ el_status el_attn_decode_step(el_attn_ctx *ctx,
                               void *out,
                               int32_t B, int32_t beam, int32_t n,
                               void *stream);
+
+/*
+ * Segment form of the step, for decoder-only models (section 3.2: EL-attention
+ * over the part of the history every beam shares and ordinary attention over
+ * each beam's own continuation, joined under ONE softmax).  A segment is one key
+ * set scored by the same queries; el_attn_decode_segment runs a1..a6 on it and
+ * returns, instead of the output row, what a joint softmax over several segments
+ * needs, per query row m = b*beam + j and head i:
+ *
+ *   seg_A     [B*beam, heads*d_k]  float32, device: the segment's own head output
+ *             sum_t p_t (H_t W_i^V + b_i^V) with p the softmax INSIDE the segment
+ *             (Eq. 8 before W^O);
+ *   seg_lse   [B*beam, heads]      float32, device: log sum_t exp(s_t) with
+ *             s_t = Q_i (H_t W_i^K + b_i^K)^T / sqrt(d_k)  in natural-log units.
+ *             The key-bias term of Eq. 7 is constant within a segment but is part
+ *             of s, so this value is directly comparable with the log-sum-exp of
+ *             any ordinary attention over projected keys (a per-beam cache a caller
+ *             keeps for the generated suffix, or another segment of this library).
+ *
+ * el_attn_merge_segments joins 1..el_attn_max_segments() segments of the same
+ * query rows and finishes the step:
+ *
+ *   w_s = exp(lse_s) / sum_s' exp(lse_s')   (evaluated relative to max_s lse_s),
+ *   A = sum_s w_s seg_A_s,   out = A . W^O + b^O                 (Eq. 2)
+ *
+ * which equals multi-head attention over the union of the segments' keys.  The
+ * segments may come from calls with different (B, beam) factorizations of the
+ * same B*beam rows: a shared prefix as (B, beam) and a per-beam suffix as
+ * (B*beam, 1) (section 3.1.1).  A segment whose lse is -inf is ignored.  seg_A and
+ * seg_lse passed to merge are HOST arrays of nseg device pointers, read during
+ * the call only.  Other arguments as for el_attn_decode_step.  Both calls use the
+ * bound workspace and never allocate.
+ *
+ * Errors: as el_attn_decode_step, plus INVALID_ARG for null outputs, nseg outside
+ * [1, el_attn_max_segments()] or a null segment pointer.
+ */
+el_status el_attn_decode_segment(el_attn_ctx *ctx,
+                                 const void *H, int64_t H_batch_stride,
+                                 const int32_t *lengths,
+                                 const void *queries,
+                                 float *seg_A, float *seg_lse,
+                                 int32_t B, int32_t beam, int32_t n,
+                                 void *stream);
+el_status el_attn_merge_segments(el_attn_ctx *ctx, int32_t nseg,
+                                 const float *const *seg_A,
+                                 const float *const *seg_lse,
+                                 void *out,
+                                 int32_t B, int32_t beam,
+                                 void *stream);
+int32_t el_attn_max_segments(void);
 
 /*
  * Diagnostic export of steps a1+a2 alone (Eq. 5, EL-Q_i = (Q W_i^Q + b_i^Q)(W_i^K)^T,

@@ -9,6 +9,9 @@ module compiles it with gcc on first use and marshals numpy arrays to it.
 ``mha_reference``  multi-head attention by its definition (Eq. 1, Eq. 2/6).
 ``el_reference``   the same quantity in the evaluation order of Eq. 9; used by
                    the tests to check the losslessness identity on the oracle.
+``segment_reference``  per-(row, head) log-sum-exp of the scores and head outputs of ordinary attention
+                   over one key set, by definition (Eq. 1, Eq. 6/7), for the joint softmax of
+                   section 3.2; ``join_segments_reference`` joins them and applies W^O.
 ``gather_batch_reference``  the state gather between decode steps (section 3.1.1's
                    state, re-ordered / compacted by the search), by its definition.
 """
@@ -142,3 +145,62 @@ def gather_batch_reference(H_src, lengths_src, index, H_dst_before):
         for t in range(int(lens[src])):
             out[i, t, :] = H_src[src, t, :]
     return out, new_lens
+
+
+def segment_reference(H, lengths, queries, Wq, bq, Wk, bk, Wv, bv, *, heads, d_k):
+    """Ordinary attention over one key set, left unjoined (section 3.2 combines such pieces under one softmax).
+
+    Per query row m = b*beam + j and head i, with K_i = H_b W_i^K + b_i^K, V_i = H_b W_i^V + b_i^V (Eq. 6) and
+    s_t = Q_i K_i[t]^T / sqrt(d_k) for t < lengths[b] (Eq. 1):
+        lse[m, i] = log sum_t exp(s_t)            seg_A[m, i*d_k:(i+1)*d_k] = softmax(s) V_i
+    Everything in float64; returns (seg_A [B*beam, h*d_k], lse [B*beam, h]).
+    """
+    H = np.asarray(H, dtype=np.float64)
+    q = np.asarray(queries, dtype=np.float64)
+    B, n, d_m = H.shape
+    beam = q.shape[1]
+    hd = heads * d_k
+    zeros = np.zeros(hd)
+    bq, bk, bv = [zeros if b is None else np.asarray(b, dtype=np.float64) for b in (bq, bk, bv)]
+    Wq, Wk, Wv = [np.asarray(W, dtype=np.float64) for W in (Wq, Wk, Wv)]
+    lens = np.full(B, n, dtype=np.int64) if lengths is None else np.asarray(lengths, dtype=np.int64)
+    seg_A = np.zeros((B * beam, hd))
+    lse = np.zeros((B * beam, heads))
+    for b in range(B):
+        Hb = H[b, :lens[b]]
+        K = Hb @ Wk + bk
+        V = Hb @ Wv + bv
+        for j in range(beam):
+            Q = q[b, j] @ Wq + bq
+            for i in range(heads):
+                cols = slice(i * d_k, (i + 1) * d_k)
+                s = K[:, cols] @ Q[cols] / np.sqrt(d_k)
+                m = s.max()
+                e = np.exp(s - m)
+                lse[b * beam + j, i] = m + np.log(e.sum())
+                seg_A[b * beam + j, cols] = (e / e.sum()) @ V[:, cols]
+    return seg_A, lse
+
+
+def join_segments_reference(segments, Wo, bo, *, heads, d_k):
+    """One softmax over the union of the segments' keys, then Eq. 2's output projection.
+
+    segments: list of (seg_A, lse) as segment_reference returns them, all over the same query rows.
+    A softmax over a union of key sets is the mixture of the per-set softmaxes with weights
+    proportional to each set's sum of exponentials, exp(lse_s).  Returns out [rows, d_m] float64.
+    """
+    Wo = np.asarray(Wo, dtype=np.float64)
+    rows = segments[0][0].shape[0]
+    A = np.zeros((rows, heads * d_k))
+    for r in range(rows):
+        for i in range(heads):
+            cols = slice(i * d_k, (i + 1) * d_k)
+            M = max(l[r, i] for _, l in segments)
+            w = np.array([np.exp(l[r, i] - M) for _, l in segments])
+            w /= w.sum()
+            for (sA, _), ws in zip(segments, w):
+                A[r, cols] += ws * sA[r, cols]
+    out = A @ Wo
+    if bo is not None:
+        out = out + np.asarray(bo, dtype=np.float64)
+    return out

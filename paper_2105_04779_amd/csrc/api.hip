@@ -56,7 +56,8 @@ Workspace carve(const el_attn_ctx *c)
 
 void free_weights(el_attn_ctx *c)
 {
-    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, c->w.WqT, c->w.WkH, c->w.WvT, c->w.WoT, (void *)c->w.c_out};
+    void *ptrs[] = {c->w.Wq, c->w.Wk, c->w.Wv, c->w.Wo, c->w.bq, c->w.WqT, c->w.WkH, c->w.WvT, c->w.WoT, (void *)c->w.c_out,
+                    (void *)c->w.bk32, (void *)c->w.bv32, (void *)c->w.bo32};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     std::memset(&c->w, 0, sizeof(c->w));
@@ -121,7 +122,6 @@ el_status el_attn_prepare(const el_attn_config *cfg,
                           const void *Wv, const void *bv, const void *Wo, const void *bo,
                           void *stream, el_attn_ctx **out_ctx)
 {
-    (void)bk; // cancels in the softmax (Eq. 7): accepted, never read
     if (out_ctx) *out_ctx = nullptr;
     if (!cfg || !out_ctx || !Wq || !Wk || !Wv || !Wo) return EL_ERR_INVALID_ARG;
     if (cfg->heads < 1 || cfg->d_model < 1 || cfg->d_k < 1) return EL_ERR_INVALID_ARG;
@@ -164,6 +164,14 @@ el_status el_attn_prepare(const el_attn_config *cfg,
         free_weights(c); delete c; return EL_ERR_ALLOC;
     }
     if (launch_cout(c, bv, bo, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+    // fp32 copies of the three biases the segment form needs (b^K enters its statistics, Eq. 7)
+    struct { float **dst; const void *src; int n; } vecs[] = {
+        {&c->w.bk32, bk, c->hd}, {&c->w.bv32, bv, c->hd}, {&c->w.bo32, bo, cfg->d_model},
+    };
+    for (auto &v : vecs) {
+        if (hipMalloc((void **)v.dst, (size_t)v.n * sizeof(float)) != hipSuccess) { free_weights(c); delete c; return EL_ERR_ALLOC; }
+        if (launch_vec_f32(cfg->dtype, v.src, *v.dst, v.n, s) != hipSuccess) { free_weights(c); delete c; return EL_ERR_HIP; }
+    }
     c->use_mfma_gemm = (c->use_mfma_core && gemm_mfma_supported(cfg->dtype, cfg->d_model, cfg->d_k)) ? 1 : 0;
     if (c->use_mfma_gemm) {
         // transposed copies so that every MFMA operand is contiguous along k; everything after a1 runs
@@ -232,23 +240,21 @@ el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq
     return EL_OK;
 }
 
-el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_stride,
-                              const int32_t *lengths, const void *queries, void *out,
-                              int32_t B, int32_t beam, int32_t n, void *stream)
+// a1..a6 of one step; on return the workspace holds the projected queries, the key-range statistics and
+// the head outputs A (without b^V), in the formats `fmt` names.
+struct StepFormats {
+    bool a_f16, qp_f16;     // element type of A and of the projected queries in the workspace
+    int parts, Rstride;     // shape of the key-range statistics [B, parts, Rstride, 2]
+    float ml_to_nat;        // ln 2 where the statistics' maxima are in log2 units
+    float c_to_nat;         // ln 2 where the projected queries carry log2(e)
+};
+
+static el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s, StepFormats *fmt)
 {
-    el_status st = check_step_args(ctx, queries, B, beam);
-    if (st != EL_OK) return st;
-    if (!H || !out) return EL_ERR_INVALID_ARG;
-    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
-    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
-    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
-
-    hipStream_t s = (hipStream_t)stream;
-    const Workspace ws = carve(ctx);
-    const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
-
+    constexpr float kLn2 = 0.6931471805599453f;
     if (el_attn_uses_mfma(ctx)) {
         const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus);
+        fmt->parts = pl.parts; fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
         // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
         const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
         if (ctx->use_mfma_gemm) {
@@ -267,9 +273,9 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
             ctx->ev_used++;
         }
         if (ctx->use_mfma_gemm) {
-            // merge of the partials fused into a6, then a7
+            // merge of the partials fused into a6
             if (launch_vproj_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
-            if (launch_oproj_mfma(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+            fmt->a_f16 = fmt->qp_f16 = true; fmt->c_to_nat = kLn2;
             return EL_OK;
         }
         if (launch_merge_exp2(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
@@ -277,6 +283,7 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
         if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
         if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
         const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
+        fmt->parts = parts; fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
         const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
         if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
         if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
@@ -286,11 +293,94 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
         }
         if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
     }
-    // a6, a7
     if (launch_vproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
-    if (launch_oproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    fmt->a_f16 = fmt->qp_f16 = false; fmt->c_to_nat = 1.f;
     return EL_OK;
 }
+
+static el_status run_a7(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s)
+{
+    const hipError_t e = (el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm) ? launch_oproj_mfma(ctx, p, ws, bias32, s)
+                                                                       : launch_oproj_generic(ctx, p, ws, bias32, s);
+    return e == hipSuccess ? EL_OK : EL_ERR_HIP;
+}
+
+static el_status check_keys(const el_attn_ctx *ctx, const void *H, int64_t H_batch_stride, int32_t n)
+{
+    if (!H) return EL_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
+    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
+    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
+    return EL_OK;
+}
+
+el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_stride,
+                              const int32_t *lengths, const void *queries, void *out,
+                              int32_t B, int32_t beam, int32_t n, void *stream)
+{
+    el_status st = check_step_args(ctx, queries, B, beam);
+    if (st != EL_OK) return st;
+    if (!out) return EL_ERR_INVALID_ARG;
+    if ((st = check_keys(ctx, H, H_batch_stride, n)) != EL_OK) return st;
+
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
+    StepFormats fmt;
+    if ((st = run_a1_to_a6(ctx, p, ws, s, &fmt)) != EL_OK) return st;
+    return run_a7(ctx, p, ws, ctx->w.c_out, s);
+}
+
+el_status el_attn_decode_segment(el_attn_ctx *ctx, const void *H, int64_t H_batch_stride,
+                                 const int32_t *lengths, const void *queries,
+                                 float *seg_A, float *seg_lse,
+                                 int32_t B, int32_t beam, int32_t n, void *stream)
+{
+    el_status st = check_step_args(ctx, queries, B, beam);
+    if (st != EL_OK) return st;
+    if (!seg_A || !seg_lse) return EL_ERR_INVALID_ARG;
+    if ((st = check_keys(ctx, H, H_batch_stride, n)) != EL_OK) return st;
+
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, nullptr, B, beam, n);
+    StepFormats fmt;
+    if ((st = run_a1_to_a6(ctx, p, ws, s, &fmt)) != EL_OK) return st;
+    SegFinishArgs f;
+    f.A = ws.A; f.Qp = ws.Qp; f.ML = ws.ML; f.bk32 = ctx->w.bk32; f.bv32 = ctx->w.bv32;
+    f.seg_A = seg_A; f.seg_lse = seg_lse;
+    f.beam = beam; f.heads = p.heads; f.d_k = p.d_k; f.hd = p.hd; f.parts = fmt.parts; f.Rstride = fmt.Rstride;
+    f.ml_to_nat = fmt.ml_to_nat; f.c_to_nat = fmt.c_to_nat;
+    if (launch_seg_finish(f, fmt.a_f16, fmt.qp_f16, B * beam, s) != hipSuccess) return EL_ERR_HIP;
+    return EL_OK;
+}
+
+el_status el_attn_merge_segments(el_attn_ctx *ctx, int32_t nseg, const float *const *seg_A,
+                                 const float *const *seg_lse, void *out,
+                                 int32_t B, int32_t beam, void *stream)
+{
+    if (!ctx || !seg_A || !seg_lse || !out) return EL_ERR_INVALID_ARG;
+    if (nseg < 1 || nseg > kMaxSegments) return EL_ERR_INVALID_ARG;
+    if (B < 1 || beam < 1 || B > ctx->cfg.max_batch || beam > ctx->cfg.max_beam) return EL_ERR_INVALID_ARG;
+    for (int i = 0; i < nseg; ++i)
+        if (!seg_A[i] || !seg_lse[i]) return EL_ERR_INVALID_ARG;
+    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, nullptr, 0, nullptr, nullptr, out, B, beam, 1);
+    const bool f16_path = el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm;
+    SegMergeArgs m;
+    for (int i = 0; i < kMaxSegments; ++i) {
+        m.A[i] = i < nseg ? seg_A[i] : nullptr;
+        m.lse[i] = i < nseg ? seg_lse[i] : nullptr;
+    }
+    m.A_out = ws.A; m.nseg = nseg; m.heads = p.heads; m.d_k = p.d_k; m.hd = p.hd;
+    if (launch_seg_merge(m, f16_path, B * beam, s) != hipSuccess) return EL_ERR_HIP;
+    return run_a7(ctx, p, ws, ctx->w.bo32, s);   // b^V is already inside every segment's A
+}
+
+int32_t el_attn_max_segments(void) { return kMaxSegments; }
 
 static void free_events(el_attn_ctx *ctx)
 {

@@ -79,6 +79,7 @@ struct Weights {    // library-owned copies in the storage dtype
     void *WqT;                      // (W^Q)^T in the storage dtype (16-bit dtypes only)
     void *WkH, *WvT, *WoT;          // W^K, (W^V)^T, (W^O)^T in fp16 (converted from bf16 when needed)
     float *c_out;                   // [d_m] = b_o + b_v . W_o, fp32
+    float *bk32, *bv32, *bo32;      // [h*d_k], [h*d_k], [d_m] in fp32 (zeros when absent): only the segment form reads them
 };
 
 } // namespace el
@@ -112,7 +113,27 @@ hipError_t launch_elq_generic(const el_attn_ctx *ctx, const Problem &p, const fl
 hipError_t launch_core_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, hipStream_t s);
 hipError_t launch_merge_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int parts, int Rstride, hipStream_t s);
 hipError_t launch_vproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
-hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
+hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s);
+hipError_t launch_vec_f32(int dtype, const void *src, float *dst, int n, hipStream_t s);
+// segment form (decoder-only models): statistics + biased head outputs of one segment; merge of several
+struct SegFinishArgs {
+    const void *A;            // [rows, hd] fp16 or fp32: the segment's normalised head outputs without b^V
+    const void *Qp;           // [rows, hd] fp16 or fp32: projected queries as a1 left them (scaled)
+    const float *ML;          // [B, parts, Rstride, 2] key-range statistics
+    const float *bk32, *bv32;
+    float *seg_A, *seg_lse;
+    int beam, heads, d_k, hd, parts, Rstride;
+    float ml_to_nat, c_to_nat; // factors that turn ML's maxima / the key-bias dot product into natural-log units
+};
+constexpr int kMaxSegments = 4;
+struct SegMergeArgs {
+    const float *A[kMaxSegments];
+    const float *lse[kMaxSegments];
+    void *A_out;              // [rows, hd] fp16 or fp32
+    int nseg, heads, d_k, hd;
+};
+hipError_t launch_seg_finish(const SegFinishArgs &a, bool a_f16, bool qp_f16, int rows, hipStream_t s);
+hipError_t launch_seg_merge(const SegMergeArgs &a, bool out_f16, int rows, hipStream_t s);
 
 // MFMA attention core -- core_ds.hip (column-split kernel), core_mfma.hip (planning, launch, helpers)
 struct CoreArgs {
@@ -145,6 +166,6 @@ hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t 
 hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, float scale, hipStream_t s);
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s);
 hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
-hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s);
+hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s);
 
 } // namespace el

@@ -445,10 +445,10 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
 }
 
 // a7: out = A . W^O + c_out
-hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s)
+hipError_t launch_oproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s)
 {
     GemmArgs g = base_args(p);
-    g.A = ws.A; g.Bt = ctx->w.WoT; g.C = p.out; g.bias32 = ctx->w.c_out;
+    g.A = ws.A; g.Bt = ctx->w.WoT; g.C = p.out; g.bias32 = bias32;
     g.N = p.d_m; g.K = p.hd; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
     if (p.out_dtype == EL_F32) return launch_slab<false, C_F32>(g, s);
     if (p.dtype == EL_BF16) return launch_slab<false, C_BF16>(g, s);

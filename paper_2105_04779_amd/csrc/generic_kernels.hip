@@ -290,16 +290,111 @@ hipError_t launch_vproj_generic(const el_attn_ctx *ctx, const Problem &p, const 
     return hipGetLastError();
 }
 
-hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s)
+hipError_t launch_oproj_generic(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s)
 {
     const dim3 grid(cdiv(p.d_m, kBlock), p.B * p.beam), block(kBlock);
     EL_DISPATCH_DTYPE(p.dtype,
         if (p.out_dtype == EL_F32)
             hipLaunchKernelGGL((k_oproj<T, float>), grid, block, 0, s, (const float *)ws.A, (const T *)ctx->w.Wo,
-                               (const float *)ctx->w.c_out, (float *)p.out, p.d_m, p.hd);
+                               bias32, (float *)p.out, p.d_m, p.hd);
         else
             hipLaunchKernelGGL((k_oproj<T, T>), grid, block, 0, s, (const float *)ws.A, (const T *)ctx->w.Wo,
-                               (const float *)ctx->w.c_out, (T *)p.out, p.d_m, p.hd));
+                               bias32, (T *)p.out, p.d_m, p.hd));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 copy of a bias vector (zeros when it is absent)
+template <typename T>
+__global__ void k_vec_f32(const T *__restrict__ src, float *__restrict__ dst, int n)
+{
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) dst[i] = src ? to_f32(src[i]) : 0.f;
+}
+
+hipError_t launch_vec_f32(int dtype, const void *src, float *dst, int n, hipStream_t s)
+{
+    EL_DISPATCH_DTYPE(dtype,
+        hipLaunchKernelGGL((k_vec_f32<T>), dim3(cdiv(n, kBlock)), dim3(kBlock), 0, s, (const T *)src, dst, n));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Segment form of the step (section 3.2: one softmax over EL-attention on a shared prefix and ordinary
+// attention on each beam's own continuation).  After a1..a6 on one key set, per (query row, head):
+//   seg_A   = A + b^V           the segment's own normalised head output (Eq. 8 with the probabilities
+//                               summing to one inside the segment)
+//   seg_lse = log sum_t exp s_t for s = Q_i K_i^T / sqrt(d_k) INCLUDING Eq. 7's key-bias term Q_i (b_i^K)^T,
+//                               which is constant inside a segment (and is dropped by the step itself) but
+//                               is part of the scores ordinary attention reports
+// The key-range statistics (reference exponent, sum relative to it) are folded by the log-sum-exp rule
+// exactly as the merge of the partials does.
+template <typename TA, typename TQ>
+__global__ void k_seg_finish(const SegFinishArgs a)
+{
+    const int cg = blockIdx.x * kBlock + threadIdx.x;
+    const int m = blockIdx.y;
+    if (cg >= a.hd) return;
+    a.seg_A[(size_t)m * a.hd + cg] = to_f32(((const TA *)a.A)[(size_t)m * a.hd + cg]) + a.bv32[cg];
+    if (cg % a.d_k != 0) return;
+    const int i = cg / a.d_k, b = m / a.beam, j = m % a.beam, r = i * a.beam + j;
+    float M = -INFINITY;
+    for (int p = 0; p < a.parts; ++p) {
+        const float *ml = a.ML + (((size_t)b * a.parts + p) * a.Rstride + r) * 2;
+        if (ml[1] > 0.f) M = fmaxf(M, ml[0]);
+    }
+    float L = 0.f;
+    for (int p = 0; p < a.parts; ++p) {
+        const float *ml = a.ML + (((size_t)b * a.parts + p) * a.Rstride + r) * 2;
+        if (ml[1] > 0.f) L += expf((ml[0] - M) * a.ml_to_nat) * ml[1];
+    }
+    float c = 0.f;
+    const TQ *q = (const TQ *)a.Qp + (size_t)m * a.hd + (size_t)i * a.d_k;
+    for (int k = 0; k < a.d_k; ++k) c = fmaf(to_f32(q[k]), a.bk32[i * a.d_k + k], c);
+    a.seg_lse[(size_t)m * a.heads + i] = L > 0.f ? M * a.ml_to_nat + logf(L) + c * a.c_to_nat : -INFINITY;
+}
+
+hipError_t launch_seg_finish(const SegFinishArgs &a, bool a_f16, bool qp_f16, int rows, hipStream_t s)
+{
+    const dim3 grid(cdiv(a.hd, kBlock), rows), block(kBlock);
+    if (a_f16 && qp_f16) hipLaunchKernelGGL((k_seg_finish<f16_t, f16_t>), grid, block, 0, s, a);
+    else if (!a_f16 && !qp_f16) hipLaunchKernelGGL((k_seg_finish<float, float>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// One softmax over the union of the segments' keys, per (row, head):
+//   w_s = exp(lse_s - max_s' lse_s') / sum_s' exp(lse_s' - max),   A = sum_s w_s seg_A_s      (then a7 on A)
+template <typename TO>
+__global__ void k_seg_merge(const SegMergeArgs a)
+{
+    const int cg = blockIdx.x * kBlock + threadIdx.x;
+    const int m = blockIdx.y;
+    if (cg >= a.hd) return;
+    const int i = cg / a.d_k;
+    float ls[kMaxSegments], M = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < kMaxSegments; ++s) {
+        ls[s] = s < a.nseg ? a.lse[s][(size_t)m * a.heads + i] : -INFINITY;
+        M = fmaxf(M, ls[s]);
+    }
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxSegments; ++s) {
+        if (s < a.nseg && ls[s] > -INFINITY) {
+            const float w = expf(ls[s] - M);
+            num = fmaf(w, a.A[s][(size_t)m * a.hd + cg], num);
+            den += w;
+        }
+    }
+    from_f32(den > 0.f ? num / den : 0.f, (TO *)a.A_out + (size_t)m * a.hd + cg);
+}
+
+hipError_t launch_seg_merge(const SegMergeArgs &a, bool out_f16, int rows, hipStream_t s)
+{
+    const dim3 grid(cdiv(a.hd, kBlock), rows), block(kBlock);
+    if (out_f16) hipLaunchKernelGGL((k_seg_merge<f16_t>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_seg_merge<float>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "el_attn_uses_mfma",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
     "el_attn_gather_batch",
+    "el_attn_decode_segment", "el_attn_merge_segments", "el_attn_max_segments",
     "el_attn_destroy", "el_attn_status_string", "el_attn_version",
 )
 
@@ -74,6 +75,12 @@ def _load():
     lib.el_attn_core_timing_read.restype = ctypes.c_int
     lib.el_attn_gather_batch.argtypes = [ctypes.c_int, i32, vp, i64, vp, i32, vp, i64, vp, i32, vp, i32, vp]
     lib.el_attn_gather_batch.restype = ctypes.c_int
+    lib.el_attn_decode_segment.argtypes = [vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.el_attn_decode_segment.restype = ctypes.c_int
+    lib.el_attn_merge_segments.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, i32, vp]
+    lib.el_attn_merge_segments.restype = ctypes.c_int
+    lib.el_attn_max_segments.argtypes = []
+    lib.el_attn_max_segments.restype = i32
     lib.el_attn_destroy.argtypes = [vp]
     lib.el_attn_destroy.restype = ctypes.c_int
     lib.el_attn_status_string.argtypes = [ctypes.c_int]
@@ -141,6 +148,24 @@ def el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B
                          H_dst, dst_batch_stride, lengths_dst, B_dst, index, n, stream=None) -> int:
     return lib.el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B_src,
                                     H_dst, dst_batch_stride, lengths_dst, B_dst, index, n, stream)
+
+
+def el_attn_decode_segment(ctx, H, H_batch_stride, lengths, queries, seg_A, seg_lse, B, beam, n, stream=None) -> int:
+    return lib.el_attn_decode_segment(ctx, H, H_batch_stride, lengths, queries, seg_A, seg_lse, B, beam, n, stream)
+
+
+def el_attn_merge_segments(ctx, nseg, seg_A, seg_lse, out, B, beam, stream=None) -> int:
+    """seg_A, seg_lse: sequences of device addresses (int, c_void_p or None), or None."""
+    def arr(ptrs):
+        if ptrs is None:
+            return None
+        vals = [p.value if isinstance(p, ctypes.c_void_p) else p for p in ptrs]
+        return (ctypes.c_void_p * max(len(vals), 1))(*vals)
+    return lib.el_attn_merge_segments(ctx, nseg, arr(seg_A), arr(seg_lse), out, B, beam, stream)
+
+
+def el_attn_max_segments() -> int:
+    return int(lib.el_attn_max_segments())
 
 
 def el_attn_core_timing_enable(ctx, max_steps) -> int:
@@ -264,6 +289,42 @@ class ElAttention:
                                  _ptr(queries), _ptr(out), B, beam, n, _stream_handle())
         if st != EL_OK:
             raise ElAttnError(st, "el_attn_decode_step")
+        return out
+
+    def decode_segment(self, H, lengths, queries):
+        """a1..a6 on one key set: returns (seg_A [B*beam, h*d_k], seg_lse [B*beam, h]) in fp32."""
+        torch = self._torch
+        B, n, d_m = H.shape
+        beam = queries.shape[1]
+        if H.stride(2) != 1 or H.stride(1) != d_m:
+            raise ValueError("rows of H must be contiguous with stride d_m")
+        if not queries.is_contiguous():
+            raise ValueError("queries must be contiguous")
+        if lengths is not None and lengths.dtype != torch.int32:
+            raise ValueError("lengths must be int32")
+        hd = self.cfg.heads * self.cfg.d_k
+        seg_A = torch.empty((B * beam, hd), dtype=torch.float32, device=H.device)
+        seg_lse = torch.empty((B * beam, self.cfg.heads), dtype=torch.float32, device=H.device)
+        st = el_attn_decode_segment(self.ctx, _ptr(H), H.stride(0) if B > 1 else n * d_m, _ptr(lengths),
+                                    _ptr(queries), _ptr(seg_A), _ptr(seg_lse), B, beam, n, _stream_handle())
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_decode_segment")
+        return seg_A, seg_lse
+
+    def merge_segments(self, segments, B, beam, out=None):
+        """segments: list of (seg_A, seg_lse) fp32 device tensors over the same B*beam rows.  Returns out [B,beam,d_m]."""
+        torch = self._torch
+        for A, S in segments:
+            if A.dtype != torch.float32 or S.dtype != torch.float32 or not A.is_contiguous() or not S.is_contiguous():
+                raise ValueError("segments must be contiguous float32 tensors")
+            if A.shape[0] != B * beam or S.shape[0] != B * beam:
+                raise ValueError("every segment must cover the same B*beam query rows")
+        if out is None:
+            out = torch.empty((B, beam, self.d_m), dtype=_torch_dtype(self.cfg.out_dtype), device=segments[0][0].device)
+        st = el_attn_merge_segments(self.ctx, len(segments), [_ptr(A) for A, _ in segments],
+                                    [_ptr(S) for _, S in segments], _ptr(out), B, beam, _stream_handle())
+        if st != EL_OK:
+            raise ElAttnError(st, "el_attn_merge_segments")
         return out
 
     def core_timing(self, max_steps: int):

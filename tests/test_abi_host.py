@@ -73,6 +73,9 @@ def test_null_context_is_rejected_everywhere(ea):
     assert ea.el_attn_core_timing_enable(None, 4) == I
     assert ea.el_attn_core_timing_read(None, 4)[0] == I
     assert ea.el_attn_destroy(None) == I
+    assert ea.el_attn_decode_segment(None, FAKE, 64, None, FAKE, FAKE, FAKE, 1, 1, 1) == I
+    assert ea.el_attn_merge_segments(None, 1, [FAKE], [FAKE], FAKE, 1, 1) == I
+    assert 1 <= ea.el_attn_max_segments() <= 16
 
 
 def test_prepare_without_a_device_reports_hip_error(ea):

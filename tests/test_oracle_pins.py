@@ -258,3 +258,79 @@ def test_gather_reference_equals_fancy_indexing_on_full_lengths():
     # an index outside the source leaves its destination alone
     out, lens = oracle.gather_batch_reference(H, L, np.array([9, -1, 2], dtype=np.int32), before[:3])
     assert np.all(out[0] == -7.0) and np.all(out[1] == -7.0) and lens.tolist() == [0, 0, 3]
+
+
+# --------------------------------------------------------------------------------------
+# segment form (section 3.2: one softmax over a shared prefix and per-beam continuations)
+# --------------------------------------------------------------------------------------
+def _segment(p, kw, **override):
+    q = dict(p)
+    q.update(override)
+    return oracle.segment_reference(q["H"], q["lengths"], q["queries"], q["Wq"], q["bq"], q["Wk"], q["bk"],
+                                    q["Wv"], q["bv"], **kw)
+
+
+def test_one_segment_joined_is_plain_attention():
+    p, kw = rand_problem(41, B=2, beam=3, h=2, d_m=8, d_k=4, n=6, lengths=[6, 4])
+    seg = _segment(p, kw)
+    got = oracle.join_segments_reference([seg], p["Wo"], p["bo"], **kw)
+    ref = run(oracle.mha_reference, p, kw).reshape(got.shape)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_segment_log_sum_exp_is_that_of_the_biased_scores():
+    # scores retyped with einsum over explicitly built keys; scipy's logsumexp as the independent routine
+    from scipy.special import logsumexp
+    p, kw = rand_problem(42, B=2, beam=2, h=2, d_m=8, d_k=4, n=5)
+    _, lse = _segment(p, kw)
+    K = (p["H"] @ p["Wk"] + p["bk"]).reshape(2, 5, 2, 4)
+    Q = (p["queries"] @ p["Wq"] + p["bq"]).reshape(2, 2, 2, 4)
+    s = np.einsum("bjic,btic->bjit", Q, K) / 2.0   # sqrt(d_k) = 2
+    np.testing.assert_allclose(lse, logsumexp(s, axis=-1).reshape(4, 2), rtol=1e-13)
+    # the key bias shifts it by Q_i . b_i^K / sqrt(d_k) (Eq. 7) and leaves seg_A alone
+    A0, l0 = _segment(p, kw, bk=None)
+    A1, l1 = _segment(p, kw)
+    shift = np.einsum("bjic,ic->bji", Q, p["bk"].reshape(2, 4)).reshape(4, 2) / 2.0
+    np.testing.assert_allclose(l1 - l0, shift, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(A1, A0, rtol=1e-12, atol=1e-14)
+
+
+def test_single_key_segment_returns_its_value_row_and_its_score():
+    p, kw = rand_problem(43, B=1, beam=2, h=2, d_m=8, d_k=4, n=3, lengths=[1])
+    A, lse = _segment(p, kw)
+    v = p["H"][0, 0] @ p["Wv"] + p["bv"]
+    np.testing.assert_allclose(A, np.stack([v, v]), rtol=1e-13)
+    k = (p["H"][0, 0] @ p["Wk"] + p["bk"]).reshape(2, 4)
+    Q = (p["queries"][0] @ p["Wq"] + p["bq"]).reshape(2, 2, 4)
+    np.testing.assert_allclose(lse, (Q * k).sum(-1) / 2.0, rtol=1e-13)
+
+
+@pytest.mark.parametrize("x,n1,n2", [(1, 4, 3), (3, 5, 2), (2, 1, 1)])
+def test_prefix_and_per_beam_suffix_joined_equal_attention_over_the_concatenation(x, n1, n2):
+    # shared prefix scored as (B, beam=x); each beam's own continuation as (B*x, beam=1)
+    B = 2
+    p, kw = rand_problem(44 + x, B=B, beam=x, h=2, d_m=8, d_k=4, n=n1,
+                         lengths=np.random.default_rng(x).integers(1, n1 + 1, B))
+    g = np.random.default_rng(100 + x)
+    H2 = g.standard_normal((B * x, n2, 8))
+    len2 = g.integers(1, n2 + 1, B * x).astype(np.int32)
+    seg1 = _segment(p, kw)
+    seg2 = _segment(p, kw, H=H2, lengths=len2, queries=p["queries"].reshape(B * x, 1, 8))
+    got = oracle.join_segments_reference([seg1, seg2], p["Wo"], p["bo"], **kw)
+    # the definition on explicitly concatenated keys, one row per beam
+    ncat = n1 + n2
+    Hcat = np.zeros((B * x, ncat, 8))
+    lcat = np.zeros(B * x, dtype=np.int32)
+    for b in range(B):
+        for j in range(x):
+            r = b * x + j
+            l1, l2 = int(p["lengths"][b]), int(len2[r])
+            Hcat[r, :l1] = p["H"][b, :l1]
+            Hcat[r, l1:l1 + l2] = H2[r, :l2]
+            lcat[r] = l1 + l2
+    ref = run(oracle.mha_reference, p, kw, H=Hcat, lengths=lcat, queries=p["queries"].reshape(B * x, 1, 8))
+    np.testing.assert_allclose(got, ref.reshape(got.shape), rtol=1e-11, atol=1e-12)
+    # dropping the key bias from ONE segment only must change the result (it no longer cancels)
+    seg2_nobk = _segment(p, kw, H=H2, lengths=len2, queries=p["queries"].reshape(B * x, 1, 8), bk=None)
+    bad = oracle.join_segments_reference([seg1, seg2_nobk], p["Wo"], p["bo"], **kw)
+    assert np.abs(bad - got).max() > 1e-4

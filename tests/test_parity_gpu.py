@@ -57,6 +57,7 @@ SMALL = [
     ("f16", 2, 3, 8, 512, 64, 77, [77, 5]),             # 24 rows: not a multiple of 16
     ("bf16", 1, 4, 12, 768, 64, 140, [140]),            # GPT-2-small width
     ("f16", 2, 2, 4, 256, 64, 64, [64, 64]),
+    ("f16", 2, 2, 4, 512, 128, 90, [90, 41]),           # head size 128: MFMA core between fp32-FMA projections
 ]
 
 
