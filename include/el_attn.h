@@ -222,7 +222,8 @@ int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);
 /*
  * Measurement aid for callers that cannot see inside a step (the benchmark): once enabled
  * with room for `max_steps` steps, every decode_step brackets its attention-core kernel
- * (steps a3-a5) with a pair of HIP events on the stream it was given.  read() waits for the
+ * (steps a3-a5) with a pair of HIP events on the stream it was given (the MFMA core's launch
+ * carries the pair itself, so it reads that dispatch's own begin and end).  read() waits for the
  * recorded events, writes the elapsed milliseconds of each step's core kernel to ms_out
  * (at most `capacity`), stores the number written in *count and forgets them.  Steps beyond
  * max_steps are not bracketed.  max_steps = 0 disables timing and releases the events.

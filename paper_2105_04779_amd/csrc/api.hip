@@ -266,12 +266,9 @@ static el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspac
         }
         // a3-a5 on MFMA; key-range partials
         const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
-        if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
-        if (launch_core_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
-        if (timed) {
-            if (hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], s) != hipSuccess) return EL_ERR_HIP;
-            ctx->ev_used++;
-        }
+        hipEvent_t ev0 = timed ? ctx->ev[2 * ctx->ev_used] : nullptr, ev1 = timed ? ctx->ev[2 * ctx->ev_used + 1] : nullptr;
+        if (launch_core_mfma(ctx, p, ws, pl, s, ev0, ev1) != hipSuccess) return EL_ERR_HIP;
+        if (timed) ctx->ev_used++;
         if (ctx->use_mfma_gemm) {
             // merge of the partials fused into a6
             if (launch_vproj_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;

@@ -29,6 +29,7 @@
 // The partial result (one per key-range split) leaves normalised by its own sum, in fp16, through
 // LDS so that every global store instruction writes 1 KB of one row.
 #include <type_traits>
+#include <hip/hip_ext.h>
 #include "el_internal.h"
 
 namespace el {
@@ -494,23 +495,32 @@ k_core_ds(const CoreArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
+// With a pair of events the launch carries them itself (they then read the dispatch's own begin and end,
+// without the command-processor time a separately recorded event adds on either side).
+template <int DM, bool BF16, int RG>
+static void launch_ds_one(const CoreArgs &a, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
+{
+    if (ev0 && ev1) hipExtLaunchKernelGGL((k_core_ds<DM, BF16, RG>), grid, dim3(256), 0, s, ev0, ev1, 0, a);
+    else hipLaunchKernelGGL((k_core_ds<DM, BF16, RG>), grid, dim3(256), 0, s, a);
+}
+
 template <int DM, bool BF16>
-static hipError_t launch_ds_t(const CoreArgs &a, int rg, hipStream_t s)
+static hipError_t launch_ds_t(const CoreArgs &a, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
     const int groups = a.B * a.S;
-    const dim3 grid(((groups + 7) / 8) * 8 * a.nblocks), block(256);
+    const dim3 grid(((groups + 7) / 8) * 8 * a.nblocks);
     switch (rg) {
-    case 1: hipLaunchKernelGGL((k_core_ds<DM, BF16, 1>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_core_ds<DM, BF16, 2>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((k_core_ds<DM, BF16, 4>), grid, block, 0, s, a); break;
+    case 1: launch_ds_one<DM, BF16, 1>(a, grid, s, ev0, ev1); break;
+    case 2: launch_ds_one<DM, BF16, 2>(a, grid, s, ev0, ev1); break;
+    default: launch_ds_one<DM, BF16, 4>(a, grid, s, ev0, ev1); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s)
+hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
-    if (d_m == 1024) return bf16 ? launch_ds_t<1024, true>(a, rg, s) : launch_ds_t<1024, false>(a, rg, s);
-    if (d_m == 512) return bf16 ? launch_ds_t<512, true>(a, rg, s) : launch_ds_t<512, false>(a, rg, s);
+    if (d_m == 1024) return bf16 ? launch_ds_t<1024, true>(a, rg, s, ev0, ev1) : launch_ds_t<1024, false>(a, rg, s, ev0, ev1);
+    if (d_m == 512) return bf16 ? launch_ds_t<512, true>(a, rg, s, ev0, ev1) : launch_ds_t<512, false>(a, rg, s, ev0, ev1);
     return hipErrorInvalidValue;
 }
 

@@ -112,14 +112,14 @@ hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Worksp
 }
 
 hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspace &ws, const CorePlan &pl,
-                            hipStream_t s)
+                            hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
     CoreArgs a;
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
     a.elq = (const f16_t *)ws.ELQ; a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
     const bool bf = p.dtype == EL_BF16;
-    return launch_core_ds(a, p.d_m, bf, pl.nrg, s);
+    return launch_core_ds(a, p.d_m, bf, pl.nrg, s, ev0, ev1);
 }
 
 hipError_t launch_merge_exp2(const el_attn_ctx *, const Problem &p, const Workspace &ws, const CorePlan &pl,

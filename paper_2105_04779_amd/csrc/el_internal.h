@@ -145,7 +145,7 @@ struct CoreArgs {
     float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
     int n, B, R, Rs, S, nblocks;
 };
-hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s);
+hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 struct CorePlan {
     int nrg;      // 16-row groups per workgroup (1, 2 or 4)
     int nblocks;  // row blocks (workgroups sharing one H range)
@@ -156,7 +156,8 @@ struct CorePlan {
 bool core_mfma_supported(int dtype, int d_m);
 CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus);
 hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
-hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
+hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s,
+                            hipEvent_t ev0, hipEvent_t ev1);   // events, if given, bracket the kernel itself
 hipError_t launch_merge_exp2(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 
 // MFMA projection GEMMs -- gemm_mfma.hip
