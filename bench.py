@@ -85,7 +85,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over batch elements with no "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -55,7 +55,7 @@ def gpu_out(layer, w, H, Q, lens):
 
 
 def record(line: str):
-    """Append one line to gpurun_out/parity_errors.txt (kept out of git) and print it."""
+    """Print one line and append it to parity_errors.txt in the run-output folder (kept out of git)."""
     import os
     print(line, flush=True)
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
