@@ -216,6 +216,15 @@ int32_t el_attn_max_splits(void);
  */
 el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups);
 
+/*
+ * What the automatic choice would be for a shape on a device with `compute_units` compute units (host
+ * arithmetic only, no device needed): rows per workgroup in groups of 16 (*row_groups) and key ranges
+ * per batch element (*splits) of the MFMA attention core.  Errors: INVALID_ARG (null outputs, sizes < 1),
+ * UNSUPPORTED (d_model other than 512 or 1024: no MFMA core).
+ */
+el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,
+                               int32_t compute_units, int32_t *row_groups, int32_t *splits);
+
 /* 1 if decode_step on this context runs the MFMA kernels, 0 if the generic fp32 ones. */
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);
 

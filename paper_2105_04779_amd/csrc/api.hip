@@ -220,6 +220,21 @@ el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups)
     return EL_OK;
 }
 
+el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,
+                               int32_t compute_units, int32_t *row_groups, int32_t *splits)
+{
+    if (!row_groups || !splits) return EL_ERR_INVALID_ARG;
+    if (B < 1 || beam < 1 || heads < 1 || n < 1 || compute_units < 1) return EL_ERR_INVALID_ARG;
+    if (d_model != 512 && d_model != 1024) return EL_ERR_UNSUPPORTED;
+    Problem p;
+    std::memset(&p, 0, sizeof(p));
+    p.B = B; p.beam = beam; p.n = n; p.heads = heads; p.d_m = d_model; p.R = heads * beam;
+    const CorePlan pl = plan_core_mfma(p, 0, 0, compute_units);
+    *row_groups = pl.nrg;
+    *splits = pl.S;
+    return EL_OK;
+}
+
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx)
 {
     return (ctx && ctx->use_mfma_core && !(ctx->cfg.flags & EL_FLAG_FORCE_GENERIC)) ? 1 : 0;

@@ -61,40 +61,54 @@ bool core_mfma_supported(int dtype, int d_m)
     return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024);
 }
 
-// How the keys are cut.  One workgroup runs per compute unit at a time; it costs a fixed set-up and
-// write-out plus its tiles, and every extra cut adds one more partial result per row to write and to
-// merge.  The split count is the one that minimises
-//     rounds(S) * (t_fixed + ceil(tiles / S) * t_tile) + S * t_partial ,   rounds = ceil(groups * S / CUs),
-// with tiles taken from the longest possible input (lengths live on the device) and the three times set
-// from measurements on MI355X: t_fixed 8 us, t_tile (0.4 + 0.3 * row groups) us per 2 KB of tile row,
-// t_partial the partials' bytes, written once and read once, at 4 TB/s.
+// How the work is cut.  A workgroup takes 16, 32 or 64 of the R = heads x beams rows that share one H
+// (row groups of 16) and one of S key ranges; one workgroup runs per compute unit at a time.  Fewer rows per
+// workgroup mean more workgroups without any partial results, but H is pulled from L2 once per row block;
+// more key ranges mean more partial results to write and to merge.  Lengths live on the device, so the plan
+// is made for the longest possible input.  It minimises a cost model fitted to measurements on MI355X
+// (d_m = 1024, microseconds; tile terms scale with d_m):
+//     rounds * (F + ceil(tiles / S) * t_tile) + S * t_merge ,        rounds = ceil(workgroups / CUs)
+//     F       = 14.5 + 0.7 S | 11.5 + 0.3 S | 10.5 + 0.15 S          set-up, expanded-query fetch, write-out
+//     t_tile  = max(compute 1.28 | 1.10 | 1.05,                      for 64 | 32 | 16 rows
+//                   1.40 * distinct tiles in flight / 256,           HBM: 256 tiles of 32 KB per 1.4 us (ragged batches)
+//                   1.05 * workgroups in flight / 256)               L2 -> compute units
+//     t_merge = 1.1 per 8.4 MB of partial rows (B * rows * d_m fp16)
 CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus)
 {
+    int nrg_max = p.R <= 16 ? 1 : (p.R <= 32 ? 2 : 4);
+    const double wide = p.d_m / 1024.0;
+    const double tiles = (p.n + 15) / 16;
+    double best = 0.0;
     CorePlan pl;
-    if (p.R <= 16) pl.nrg = 1;
-    else if (p.R <= 32) pl.nrg = 2;
-    else pl.nrg = 4;
-    if (nrg_override > 0 && nrg_override < pl.nrg) pl.nrg = nrg_override;
-    pl.nblocks = (p.R + 16 * pl.nrg - 1) / (16 * pl.nrg);
-    pl.Rs = pl.nblocks * 16 * pl.nrg;
-    int S = splits_override;
-    if (S <= 0) {
-        const double groups = (double)p.B * pl.nblocks;
-        const double tiles = (p.n + 15) / 16;
-        const double t_tile = (0.4 + 0.3 * pl.nrg) * p.d_m / 1024.0, t_fixed = 8.0;
-        const double t_partial = 2.0 * p.B * pl.Rs * (double)p.d_m * 2.0 / 4.0e6;
-        double best = 0.0;
+    pl.nrg = 0;
+    for (int nrg = nrg_max; nrg >= 1; nrg >>= 1) {
+        if (nrg_override > 0 && nrg != (nrg_override < nrg_max ? nrg_override : nrg_max)) continue;
+        const int nblocks = (p.R + 16 * nrg - 1) / (16 * nrg);
+        const int Rs = nblocks * 16 * nrg;
+        const double groups = (double)p.B * nblocks;
+        const double f0 = nrg == 4 ? 14.5 : (nrg == 2 ? 11.5 : 10.5), f1 = nrg == 4 ? 0.7 : (nrg == 2 ? 0.3 : 0.15);
+        const double t_c = (nrg == 4 ? 1.28 : (nrg == 2 ? 1.10 : 1.05)) * wide;
+        const double t_merge = 1.1 * ((double)p.B * Rs * p.d_m) / (64.0 * 64.0 * 1024.0);
         for (int c = 1; c <= kMaxParts; ++c) {
-            if (c > 1 && tiles / c < 4.0) break;          // shorter ranges are not worth a workgroup
-            const double rounds = ceil(groups * c / num_cus);
-            const double t = rounds * (t_fixed + ceil(tiles / c) * t_tile) + c * t_partial;
-            if (c == 1 || t < best) { best = t; S = c; }
+            if (splits_override > 0 && c != splits_override) continue;
+            if (splits_override <= 0 && c > 1 && tiles / c < 4.0) break;   // shorter ranges are not worth a workgroup
+            const double wgs = groups * c;
+            const double rounds = ceil(wgs / num_cus);
+            const double active = wgs < num_cus ? wgs : num_cus;
+            double t_tile = t_c;
+            t_tile = fmax(t_tile, 1.40 * wide * (active / nblocks) / 256.0);
+            t_tile = fmax(t_tile, 1.05 * wide * active / 256.0);
+            const double t = rounds * ((f0 + f1 * c) * (0.5 + 0.5 * wide) + ceil(tiles / c) * t_tile) + c * t_merge;
+            if (pl.nrg == 0 || t < best) {
+                best = t;
+                pl.nrg = nrg; pl.nblocks = nblocks; pl.Rs = Rs; pl.S = c;
+            }
         }
     }
-    if (S > kMaxParts) S = kMaxParts;
-    if (S < 1) S = 1;
-    pl.S = S;
-    pl.parts = S;
+    if (pl.nrg == 0) {   // an override outside what the shape allows: fall back to the widest block, no cut
+        pl.nrg = nrg_max; pl.nblocks = (p.R + 16 * nrg_max - 1) / (16 * nrg_max); pl.Rs = pl.nblocks * 16 * nrg_max; pl.S = 1;
+    }
+    pl.parts = pl.S;
     return pl;
 }
 

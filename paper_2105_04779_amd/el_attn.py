@@ -21,7 +21,7 @@ DTYPE_CODES = {"f32": EL_F32, "f16": EL_F16, "bf16": EL_BF16}
 EXPORTED_SYMBOLS = (
     "el_attn_prepare", "el_attn_workspace_bytes", "el_attn_bind_workspace", "el_attn_decode_step",
     "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
-    "el_attn_uses_mfma",
+    "el_attn_uses_mfma", "el_attn_plan_preview",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
     "el_attn_gather_batch",
     "el_attn_decode_segment", "el_attn_merge_segments", "el_attn_max_segments",
@@ -67,6 +67,8 @@ def _load():
     lib.el_attn_set_row_groups.restype = ctypes.c_int
     lib.el_attn_max_splits.argtypes = []
     lib.el_attn_max_splits.restype = i32
+    lib.el_attn_plan_preview.argtypes = [i32] * 6 + [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.el_attn_plan_preview.restype = ctypes.c_int
     lib.el_attn_uses_mfma.argtypes = [vp]
     lib.el_attn_uses_mfma.restype = i32
     lib.el_attn_core_timing_enable.argtypes = [vp, i32]
@@ -138,6 +140,13 @@ def el_attn_set_splits(ctx, splits) -> int:
 
 def el_attn_set_row_groups(ctx, row_groups) -> int:
     return lib.el_attn_set_row_groups(ctx, row_groups)
+
+
+def el_attn_plan_preview(B, beam, heads, d_model, n, compute_units):
+    """Returns (status, row_groups, splits)."""
+    rg, sp = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib.el_attn_plan_preview(B, beam, heads, d_model, n, compute_units, ctypes.byref(rg), ctypes.byref(sp))
+    return st, rg.value, sp.value
 
 
 def el_attn_uses_mfma(ctx) -> int:

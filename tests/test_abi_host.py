@@ -104,3 +104,27 @@ def test_gather_batch_rejects_bad_arguments_before_any_device_work(ea):
     assert call(dtype=ea.EL_F32, d_model=6, sstride=6 * 64, dstride=6 * 64) == I
     assert call(src=ctypes.c_void_p(0x10008)) == I                              # misaligned
     assert call(sstride=64 * 1024 + 4) == I                                     # batch stride breaks the 16-byte alignment
+
+
+def test_plan_preview_on_the_benchmark_shapes(ea):
+    """The automatic cut of the work, on a 256-unit device: host arithmetic only."""
+    def plan(B, beam, heads, d_m, n):
+        st, rg, sp = ea.el_attn_plan_preview(B, beam, heads, d_m, n, 256)
+        assert st == ea.EL_OK
+        return rg, sp
+    assert plan(64, 4, 16, 1024, 1024) == (4, 4)     # 64 sentences x 4 beams, long inputs: all rows, four key ranges
+    assert plan(320, 4, 16, 1024, 1024) == (4, 2)    # 320 sentences: two ranges, 2.5 rounds of workgroups
+    assert plan(512, 1, 16, 1024, 1024) == (1, 1)    # per-beam histories: 16 rows, no cut
+    assert plan(64, 4, 16, 1024, 256) == (2, 2)      # short inputs: half the rows per workgroup instead of more cuts
+    rg, sp = plan(64, 4, 16, 1024, 64)
+    assert sp == 1 and rg in (1, 2)                  # four tiles: never cut
+    for B in (1, 3, 17, 64, 100, 1000):
+        for beam in (1, 2, 4, 5, 8):
+            for n in (1, 16, 100, 1024, 4096):
+                rg, sp = plan(B, beam, 16, 1024, n)
+                assert rg in (1, 2, 4) and 1 <= sp <= ea.el_attn_max_splits()
+                assert rg <= {1: 1, 2: 2}.get(beam, 4)             # never more rows than the shape has (in 16s, padded)
+    I = ea.EL_ERR_INVALID_ARG
+    assert ea.el_attn_plan_preview(0, 4, 16, 1024, 64, 256)[0] == I
+    assert ea.el_attn_plan_preview(4, 4, 16, 1024, 64, 0)[0] == I
+    assert ea.el_attn_plan_preview(4, 4, 16, 768, 64, 256)[0] == ea.EL_ERR_UNSUPPORTED
