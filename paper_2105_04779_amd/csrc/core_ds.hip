@@ -75,15 +75,10 @@ __device__ __forceinline__ h8 frag_bf16_to_f16(h8 v)
 }
 
 
-template <int DM, bool BF16_, int RG>
+template <int DM, bool BF16, int RG>
 __global__ void __launch_bounds__(256)
 k_core_ds(const CoreArgs a)
 {
-#ifdef EL_EXP_NOCONV
-    constexpr bool BF16 = false;
-#else
-    constexpr bool BF16 = BF16_;
-#endif
     constexpr int ROWB = DM * 2;                    // bytes per tile row (2-byte elements)
     constexpr int SLOT = kTileRows16 * ROWB;        // one tile
     constexpr int NSLOT = 4;

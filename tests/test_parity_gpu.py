@@ -12,7 +12,7 @@ from helpers import TOL, gpu_out, make_layer, oracle_out, record, rel_err, to_de
 pytestmark = pytest.mark.gpu
 
 
-def run_case(w, *, lens=None, poison=True, flags=0, splits=0, scale_q=None, elements=None, tol=None):
+def run_case(w, *, lens=None, poison=True, flags=0, splits=0, row_groups=0, scale_q=None, elements=None, tol=None):
     W = wl.weights(w)
     H, Q, L = wl.batch(w, elements=elements, poison=False)
     if lens is not None:
@@ -27,10 +27,12 @@ def run_case(w, *, lens=None, poison=True, flags=0, splits=0, scale_q=None, elem
     layer = make_layer(w, W, max_batch=H.shape[0], flags=flags)
     if splits:
         layer.set_splits(splits)
+    if row_groups:
+        layer.set_row_groups(row_groups)
     y = gpu_out(layer, w, Hp, Q, L)
     err = rel_err(y, ref)
     bar = tol or TOL[w.dtype]
-    record(f"{w.name}: B={H.shape[0]} mfma={layer.uses_mfma} splits={splits} err={err:.3e} bar={bar:g}")
+    record(f"{w.name}: B={H.shape[0]} mfma={layer.uses_mfma} splits={splits} row_groups={row_groups} err={err:.3e} bar={bar:g}")
     assert err <= bar, f"{w.name}: err {err:.3e} > {bar:g}"
     layer.close()
     return y
@@ -109,6 +111,15 @@ def test_peaked_softmax_large_scores():
 def test_split_count_does_not_change_the_result(splits):
     w = wl.custom("splits", dtype="bf16", B=2, beam=4, heads=16, d_m=1024, d_k=64, n=300, index=57)
     run_case(w, lens=[300, 70], splits=splits)
+
+
+@pytest.mark.parametrize("dtype,heads,d_m,beam", [("bf16", 16, 1024, 4), ("bf16", 16, 1024, 6), ("f16", 8, 512, 7)])
+@pytest.mark.parametrize("row_groups,splits", [(1, 1), (1, 3), (2, 1), (2, 2), (2, 5), (4, 1), (4, 3), (0, 0)])
+def test_rows_per_workgroup_and_split_count_do_not_change_the_result(dtype, heads, d_m, beam, row_groups, splits):
+    # every cut the automatic plan can choose: 16, 32 or 64 rows per workgroup (one to six row blocks that
+    # share each H range) times the key ranges, on ragged lengths with a short last tile
+    w = wl.custom(f"cut_{dtype}_{heads}x{beam}", dtype=dtype, B=3, beam=beam, heads=heads, d_m=d_m, d_k=64, n=330, index=58)
+    run_case(w, lens=[330, 161, 19], splits=splits, row_groups=row_groups)
 
 
 def test_strided_batch_and_guard_bands():
