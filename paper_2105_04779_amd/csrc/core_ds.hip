@@ -112,6 +112,25 @@ k_core_ds(const CoreArgs a)
     if (group >= a.B * a.S) return;
     const int b = group / a.S, s = group % a.S;
     int len = a.lengths ? a.lengths[b] : a.n;
+
+    // ---- this wavefront's column slice of ELQ, all row groups: B operand of the score product ----
+    // Requested first: the addresses need nothing but the workgroup's coordinates, so these loads are under
+    // way while the element's length (a dependent load the tile requests have to wait for) is still coming.
+    h8 elq[RG][KC];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+        const int row = row0 + 16 * rg + r16;
+        // pad rows (row >= R) are never written by the expansion step: they read as zero here
+        const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + DS * w + 8 * g;
+        const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < KC; ++c) elq[rg][c] = zero;
+        if (row < a.R) {
+#pragma unroll
+            for (int c = 0; c < KC; ++c) elq[rg][c] = *(const h8 *)(src + 32 * c);
+        }
+    }
+
     len = min(max(len, 1), a.n);
     const int NT = (len + kTileRows16 - 1) / kTileRows16;
     const int k0 = (NT * s) / a.S, k1 = (NT * (s + 1)) / a.S;   // NT * S stays far below 2^31
@@ -172,8 +191,7 @@ k_core_ds(const CoreArgs a)
         }
     };
 
-    // ---- prologue: request two tiles, wait for the first ----
-    // the first two tiles are requested before anything else is: they take the longest to arrive
+    // ---- prologue: request two tiles (right behind the ELQ loads), wait for everything ----
     if (nloc > 0) {
         issue_dma(k0, 0);
         issue_dma(k0 + 1, 1);
@@ -205,18 +223,6 @@ k_core_ds(const CoreArgs a)
         }
     }
 
-    // ---- this wavefront's column slice of ELQ, all row groups: B operand of the score product ----
-    h8 elq[RG][KC];
-#pragma unroll
-    for (int rg = 0; rg < RG; ++rg) {
-        const int row = row0 + 16 * rg + r16;
-        // pad rows (row >= R) are never written by the expansion step: they read as zero here
-        const f16_t *src = a.elq + ((size_t)b * a.Rs + row) * DM + DS * w + 8 * g;
-        const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int c = 0; c < KC; ++c) elq[rg][c] = row < a.R ? *(const h8 *)(src + 32 * c) : zero;
-    }
-
     f16v X[MB][NB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -231,7 +237,7 @@ k_core_ds(const CoreArgs a)
     for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
         for (int c = 0; c < KC; ++c) asm volatile("" :: "v"(elq[rg][c]));
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  // ELQ and, requested before it, both tiles
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  // ELQ and, requested after it, both tiles
     if (nloc > 0) zero_ragged(k0, 0);
     __syncthreads();
 
