@@ -96,6 +96,77 @@ Problem make_problem(const el_attn_ctx *ctx, const void *H, int64_t stride, cons
     return p;
 }
 
+// a1..a6 of one step; on return the workspace holds the projected queries, the key-range statistics and
+// the head outputs A (without b^V), in the formats `fmt` names.
+struct StepFormats {
+    bool a_f16, qp_f16;     // element type of A and of the projected queries in the workspace
+    int parts, Rstride;     // shape of the key-range statistics [B, parts, Rstride, 2]
+    float ml_to_nat;        // ln 2 where the statistics' maxima are in log2 units
+    float c_to_nat;         // ln 2 where the projected queries carry log2(e)
+};
+
+el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s, StepFormats *fmt)
+{
+    constexpr float kLn2 = 0.6931471805599453f;
+    if (el_attn_uses_mfma(ctx)) {
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus);
+        fmt->parts = pl.parts; fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
+        // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
+        const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
+        if (ctx->use_mfma_gemm) {
+            if (launch_qproj_mfma(ctx, p, ws, qscale, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_elq_mfma(ctx, p, ws, pl.Rs, s) != hipSuccess) return EL_ERR_HIP;
+        } else {
+            if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+            if (launch_elq_f16(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+        }
+        // a3-a5 on MFMA; key-range partials
+        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
+        hipEvent_t ev0 = timed ? ctx->ev[2 * ctx->ev_used] : nullptr, ev1 = timed ? ctx->ev[2 * ctx->ev_used + 1] : nullptr;
+        if (launch_core_mfma(ctx, p, ws, pl, s, ev0, ev1) != hipSuccess) return EL_ERR_HIP;
+        if (timed) ctx->ev_used++;
+        if (ctx->use_mfma_gemm) {
+            // merge of the partials fused into a6
+            if (launch_vproj_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+            fmt->a_f16 = fmt->qp_f16 = true; fmt->c_to_nat = kLn2;
+            return EL_OK;
+        }
+        if (launch_merge_exp2(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
+    } else {
+        if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+        if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
+        const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
+        fmt->parts = parts; fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
+        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
+        if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
+        if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
+        if (timed) {
+            if (hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], s) != hipSuccess) return EL_ERR_HIP;
+            ctx->ev_used++;
+        }
+        if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
+    }
+    if (launch_vproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
+    fmt->a_f16 = fmt->qp_f16 = false; fmt->c_to_nat = 1.f;
+    return EL_OK;
+}
+
+el_status run_a7(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s)
+{
+    const hipError_t e = (el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm) ? launch_oproj_mfma(ctx, p, ws, bias32, s)
+                                                                       : launch_oproj_generic(ctx, p, ws, bias32, s);
+    return e == hipSuccess ? EL_OK : EL_ERR_HIP;
+}
+
+el_status check_keys(const el_attn_ctx *ctx, const void *H, int64_t H_batch_stride, int32_t n)
+{
+    if (!H) return EL_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
+    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
+    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
+    return EL_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -252,77 +323,6 @@ el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq
     const Problem p = make_problem(ctx, nullptr, 0, nullptr, queries, nullptr, B, beam, 1);
     if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
     if (launch_elq_generic(ctx, p, ws.Qp, elq_out, s) != hipSuccess) return EL_ERR_HIP;
-    return EL_OK;
-}
-
-// a1..a6 of one step; on return the workspace holds the projected queries, the key-range statistics and
-// the head outputs A (without b^V), in the formats `fmt` names.
-struct StepFormats {
-    bool a_f16, qp_f16;     // element type of A and of the projected queries in the workspace
-    int parts, Rstride;     // shape of the key-range statistics [B, parts, Rstride, 2]
-    float ml_to_nat;        // ln 2 where the statistics' maxima are in log2 units
-    float c_to_nat;         // ln 2 where the projected queries carry log2(e)
-};
-
-static el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, hipStream_t s, StepFormats *fmt)
-{
-    constexpr float kLn2 = 0.6931471805599453f;
-    if (el_attn_uses_mfma(ctx)) {
-        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus);
-        fmt->parts = pl.parts; fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
-        // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
-        const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
-        if (ctx->use_mfma_gemm) {
-            if (launch_qproj_mfma(ctx, p, ws, qscale, s) != hipSuccess) return EL_ERR_HIP;
-            if (launch_elq_mfma(ctx, p, ws, pl.Rs, s) != hipSuccess) return EL_ERR_HIP;
-        } else {
-            if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
-            if (launch_elq_f16(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
-        }
-        // a3-a5 on MFMA; key-range partials
-        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
-        hipEvent_t ev0 = timed ? ctx->ev[2 * ctx->ev_used] : nullptr, ev1 = timed ? ctx->ev[2 * ctx->ev_used + 1] : nullptr;
-        if (launch_core_mfma(ctx, p, ws, pl, s, ev0, ev1) != hipSuccess) return EL_ERR_HIP;
-        if (timed) ctx->ev_used++;
-        if (ctx->use_mfma_gemm) {
-            // merge of the partials fused into a6
-            if (launch_vproj_mfma(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
-            fmt->a_f16 = fmt->qp_f16 = true; fmt->c_to_nat = kLn2;
-            return EL_OK;
-        }
-        if (launch_merge_exp2(ctx, p, ws, pl, s) != hipSuccess) return EL_ERR_HIP;
-    } else {
-        if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
-        if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
-        const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
-        fmt->parts = parts; fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
-        const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
-        if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
-        if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
-        if (timed) {
-            if (hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], s) != hipSuccess) return EL_ERR_HIP;
-            ctx->ev_used++;
-        }
-        if (launch_merge_generic(ctx, p, ws, parts, p.R, s) != hipSuccess) return EL_ERR_HIP;
-    }
-    if (launch_vproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
-    fmt->a_f16 = fmt->qp_f16 = false; fmt->c_to_nat = 1.f;
-    return EL_OK;
-}
-
-static el_status run_a7(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const float *bias32, hipStream_t s)
-{
-    const hipError_t e = (el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm) ? launch_oproj_mfma(ctx, p, ws, bias32, s)
-                                                                       : launch_oproj_generic(ctx, p, ws, bias32, s);
-    return e == hipSuccess ? EL_OK : EL_ERR_HIP;
-}
-
-static el_status check_keys(const el_attn_ctx *ctx, const void *H, int64_t H_batch_stride, int32_t n)
-{
-    if (!H) return EL_ERR_INVALID_ARG;
-    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
-    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
-    if (!ctx->ws_base) return EL_ERR_WORKSPACE;
     return EL_OK;
 }
 
