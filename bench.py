@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
     ap.add_argument("--same-h", action="store_true", help="reuse one H buffer every step (cache-warm; not the reported protocol)")
     ap.add_argument("--layers", type=int, default=1, help="attention layers (own weights each) that read the same H in one step")
+    ap.add_argument("--check", action="store_true",
+                    help="time the diagnostic input check (one read of the valid rows of H) instead of the decode step")
     ap.add_argument("--gather", action="store_true",
                     help="state maintenance instead of the decode step: re-order 512 per-beam histories of up to 1024 rows "
                          "(GPT-2-medium widths) by parent beam; one line with the bytes moved per second")
@@ -104,6 +106,9 @@ def main():
         print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": src.numel() * 4,
                           "bytes_written_per_launch": src.numel() * 4, "launches": 10}))
         return
+    if a.check:
+        print(json.dumps(measure_check(a, torch, np, el_attn, wl)), flush=True)
+        return
     if a.gather:
         print(json.dumps(measure_gather(a, torch, np, el_attn, wl)), flush=True)
         return
@@ -160,6 +165,36 @@ def measure_gather(a, torch, np, el_attn, wl):
                        "sum_len": int(lens[index].sum()), "event_ms_per_step": e0.elapsed_time(e1) / a.steps},
             "roofline": {"bound": "hbm", "kernel": "k_gather_batch", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": moved, "avg_launch_us": ms * 1e3}}
+
+
+def measure_check(a, torch, np, el_attn, wl):
+    """The diagnostic input check on the per-beam histories of the self-attention workload: every valid row of H is
+    read once and classified.  Bound: HBM."""
+    w = wl.WORKLOADS["c5_gpt2_medium_n1024_bf16"]
+    B, n, d_m = w.B, w.n, w.d_m
+    g = torch.Generator(device="cuda").manual_seed(wl.BASE_SEED + 310)
+    H = torch.randn((B, n, d_m), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    lens = np.random.default_rng(wl.BASE_SEED + 311).integers(n // 2, n, size=B, endpoint=True).astype(np.int32)
+    Ld = torch.from_numpy(lens).cuda()
+    report = torch.empty(4, dtype=torch.int64, device="cuda")
+    for _ in range(a.warmup):
+        el_attn.check_inputs(H, Ld, report=report)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        el_attn.check_inputs(H, Ld, report=report)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    read = int(lens.sum()) * d_m * 2
+    assert report.cpu().tolist() == [0, 0, 0, int(lens.sum()) * d_m]
+    gbs = read / (ms * 1e-3) / 1e9
+    return {"metric": "input check, bytes read per second", "value": gbs, "unit": "GB/s", "n_gpus": 1,
+            "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+            "config": {"workload": "input check of per-beam histories, GPT-2-medium widths", "B": B, "n": n, "d_m": d_m,
+                       "sum_len": int(lens.sum())},
+            "roofline": {"bound": "hbm", "kernel": "k_check_inputs", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": read, "avg_launch_us": ms * 1e3}}
 
 
 def measure(a, w, torch, np, el_attn, tm, wl):

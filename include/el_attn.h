@@ -272,6 +272,27 @@ el_status el_attn_gather_batch(el_dtype dtype, int32_t d_model,
                                void *H_dst, int64_t dst_batch_stride, int32_t *lengths_dst, int32_t B_dst,
                                const int32_t *index, int32_t n, void *stream);
 
+/*
+ * Diagnostic pass over the inputs of a decode step: what the step assumes and, living in device
+ * memory, does not verify on its hot path.  One read of the valid rows of H (rows at or beyond a
+ * length are not read; a length outside [0, n] is clamped for reading) fills
+ *
+ *   report[0]  lengths outside [1, n]          (section 3.1: a softmax over no position is undefined)
+ *   report[1]  elements that are NaN or +-Inf
+ *   report[2]  finite elements with |v| > 65504: the 16-bit MFMA path converts bf16 operands to
+ *              fp16, which saturates beyond that magnitude (fp16 storage cannot hold such values)
+ *   report[3]  elements examined = sum_b min(max(len_b, 0), n) * d_model
+ *
+ *   report   [4] uint64, DEVICE memory, 8-byte aligned; cleared and filled on `stream`.
+ *   H, lengths, strides, dtype as for el_attn_gather_batch (16-byte alignment rules included).
+ *
+ * Context-free, asynchronous, allocates nothing.  Errors: INVALID_ARG (null H/report, unknown
+ * dtype, sizes < 1, B > 65535, stride < n*d_model, alignment), HIP.
+ */
+el_status el_attn_check_inputs(el_dtype dtype, int32_t d_model,
+                               const void *H, int64_t H_batch_stride, const int32_t *lengths,
+                               int32_t B, int32_t n, uint64_t *report, void *stream);
+
 /* Release the context and its packed weights (not the workspace, which the caller owns). */
 el_status el_attn_destroy(el_attn_ctx *ctx);
 

@@ -12,6 +12,7 @@ module compiles it with gcc on first use and marshals numpy arrays to it.
 ``segment_reference``  per-(row, head) log-sum-exp of the scores and head outputs of ordinary attention
                    over one key set, by definition (Eq. 1, Eq. 6/7), for the joint softmax of
                    section 3.2; ``join_segments_reference`` joins them and applies W^O.
+``check_inputs_reference``  what a decode step assumes about its inputs, counted by definition.
 ``gather_batch_reference``  the state gather between decode steps (section 3.1.1's
                    state, re-ordered / compacted by the search), by its definition.
 """
@@ -204,3 +205,28 @@ def join_segments_reference(segments, Wo, bo, *, heads, d_k):
     if bo is not None:
         out = out + np.asarray(bo, dtype=np.float64)
     return out
+
+
+def check_inputs_reference(H, lengths, n=None):
+    """Counts of what the decode step assumes about its inputs (section 3.1 needs a non-empty softmax; the 16-bit
+    path needs fp16-representable magnitudes), one element at a time over the valid rows only.
+
+    H [B, n, d_m] as float32/float64 VALUES of the stored elements (NaN/Inf allowed); lengths [B] or None.
+    Returns [lengths outside [1, n], non-finite elements, finite elements with |v| > 65504, elements examined];
+    a length outside [0, n] is clamped for the walk.
+    """
+    H = np.asarray(H)
+    B, n_rows, d_m = H.shape
+    n = n_rows if n is None else n
+    lens = np.full(B, n, dtype=np.int64) if lengths is None else np.asarray(lengths, dtype=np.int64)
+    bad_len = nonfinite = large = seen = 0
+    for b in range(B):
+        if lens[b] < 1 or lens[b] > n:
+            bad_len += 1
+        for t in range(int(min(max(lens[b], 0), n))):
+            row = H[b, t].astype(np.float64)
+            fin = np.isfinite(row)
+            nonfinite += int((~fin).sum())
+            large += int((np.abs(row[fin]) > 65504.0).sum())
+            seen += d_m
+    return [bad_len, nonfinite, large, seen]

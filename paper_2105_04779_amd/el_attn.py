@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
     "el_attn_uses_mfma", "el_attn_plan_preview",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
-    "el_attn_gather_batch",
+    "el_attn_gather_batch", "el_attn_check_inputs",
     "el_attn_decode_segment", "el_attn_merge_segments", "el_attn_max_segments",
     "el_attn_destroy", "el_attn_status_string", "el_attn_version",
 )
@@ -77,6 +77,8 @@ def _load():
     lib.el_attn_core_timing_read.restype = ctypes.c_int
     lib.el_attn_gather_batch.argtypes = [ctypes.c_int, i32, vp, i64, vp, i32, vp, i64, vp, i32, vp, i32, vp]
     lib.el_attn_gather_batch.restype = ctypes.c_int
+    lib.el_attn_check_inputs.argtypes = [ctypes.c_int, i32, vp, i64, vp, i32, i32, vp, vp]
+    lib.el_attn_check_inputs.restype = ctypes.c_int
     lib.el_attn_decode_segment.argtypes = [vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, vp]
     lib.el_attn_decode_segment.restype = ctypes.c_int
     lib.el_attn_merge_segments.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, i32, vp]
@@ -159,6 +161,10 @@ def el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B
                                     H_dst, dst_batch_stride, lengths_dst, B_dst, index, n, stream)
 
 
+def el_attn_check_inputs(dtype, d_model, H, H_batch_stride, lengths, B, n, report, stream=None) -> int:
+    return lib.el_attn_check_inputs(dtype, d_model, H, H_batch_stride, lengths, B, n, report, stream)
+
+
 def el_attn_decode_segment(ctx, H, H_batch_stride, lengths, queries, seg_A, seg_lse, B, beam, n, stream=None) -> int:
     return lib.el_attn_decode_segment(ctx, H, H_batch_stride, lengths, queries, seg_A, seg_lse, B, beam, n, stream)
 
@@ -232,6 +238,25 @@ def gather_batch(H_src, lengths_src, index, *, H_dst=None, lengths_dst=None):
     if st != EL_OK:
         raise ElAttnError(st, "el_attn_gather_batch")
     return H_dst, lengths_dst
+
+
+def check_inputs(H, lengths, report=None):
+    """Counts of what a decode step assumes about (H, lengths): returns a device int64 tensor
+    [bad lengths, non-finite elements, elements beyond the fp16 range, elements examined] (see el_attn_check_inputs)."""
+    import torch
+    if H.dim() != 3 or H.stride(2) != 1 or H.stride(1) != H.shape[2]:
+        raise ValueError("H must be [B, n, d_m] with contiguous rows")
+    code = {torch.float32: EL_F32, torch.float16: EL_F16, torch.bfloat16: EL_BF16}[H.dtype]
+    B, n, d_m = H.shape
+    if lengths is not None and lengths.dtype != torch.int32:
+        raise ValueError("lengths must be int32")
+    if report is None:
+        report = torch.empty(4, dtype=torch.int64, device=H.device)
+    st = el_attn_check_inputs(code, d_m, _ptr(H), H.stride(0) if B > 1 else n * d_m, _ptr(lengths), B, n,
+                              _ptr(report), _stream_handle())
+    if st != EL_OK:
+        raise ElAttnError(st, "el_attn_check_inputs")
+    return report
 
 
 class ElAttention:

@@ -128,3 +128,20 @@ def test_plan_preview_on_the_benchmark_shapes(ea):
     assert ea.el_attn_plan_preview(0, 4, 16, 1024, 64, 256)[0] == I
     assert ea.el_attn_plan_preview(4, 4, 16, 1024, 64, 0)[0] == I
     assert ea.el_attn_plan_preview(4, 4, 16, 768, 64, 256)[0] == ea.EL_ERR_UNSUPPORTED
+
+
+def test_check_inputs_rejects_bad_arguments_before_any_device_work(ea):
+    I = ea.EL_ERR_INVALID_ARG
+    A, Rp = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)   # never dereferenced
+
+    def call(dtype=ea.EL_BF16, d_model=1024, H=A, stride=64 * 1024, lengths=None, B=4, n=64, report=Rp):
+        return ea.el_attn_check_inputs(dtype, d_model, H, stride, lengths, B, n, report)
+
+    assert call(H=None) == I and call(report=None) == I
+    assert call(dtype=9) == I
+    for bad in (dict(d_model=0), dict(B=0), dict(n=0), dict(B=70000)):
+        assert call(**bad) == I, bad
+    assert call(stride=64 * 1024 - 8) == I                      # shorter than n rows
+    assert call(d_model=1020) == I                              # rows not a multiple of 16 bytes
+    assert call(H=ctypes.c_void_p(0x10008)) == I                # misaligned H
+    assert call(report=ctypes.c_void_p(0x20004)) == I           # misaligned report

@@ -334,3 +334,18 @@ def test_prefix_and_per_beam_suffix_joined_equal_attention_over_the_concatenatio
     seg2_nobk = _segment(p, kw, H=H2, lengths=len2, queries=p["queries"].reshape(B * x, 1, 8), bk=None)
     bad = oracle.join_segments_reference([seg1, seg2_nobk], p["Wo"], p["bo"], **kw)
     assert np.abs(bad - got).max() > 1e-4
+
+
+def test_check_inputs_reference_counts_exactly_what_was_planted():
+    # expected counts are known by construction, not computed by the function under test
+    g = np.random.default_rng(60)
+    B, n, d = 3, 7, 8
+    H = g.standard_normal((B, n, d)).astype(np.float32)
+    lens = np.array([7, 4, 0], dtype=np.int32)            # one length outside [1, n]
+    H[0, 2, 3] = np.nan; H[0, 6, 0] = np.inf; H[1, 3, 7] = -np.inf      # three non-finite, all in valid rows
+    H[1, 0, 1] = 70000.0; H[0, 0, 0] = -65505.0                          # two beyond the fp16 range
+    H[0, 1, 1] = 65504.0                                                 # exactly representable: not counted
+    H[1, 5, 2] = np.nan; H[2, 0, 0] = 1e9                                # beyond the lengths: never looked at
+    assert oracle.check_inputs_reference(H, lens) == [1, 3, 2, (7 + 4 + 0) * d]
+    assert oracle.check_inputs_reference(H, None) == [0, 4, 3, 3 * 7 * d]
+    assert oracle.check_inputs_reference(H, np.array([9, -2, 7])) == [2, 2, 2, (7 + 0 + 7) * d]   # element 1 skipped, element 2 walked

@@ -102,3 +102,48 @@ def test_per_beam_histories_full_size_sampled():
         assert torch.equal(dst[i, :L].view(torch.int16), H[int(index[i]), :L].view(torch.int16)), i
         assert bool((dst[i, L:] == 3.0).all()), i
     record(f"gather full size: B={B} n={n} d_m={d_m} sum_len={int(lens[index].sum())} bit-exact on 14 sampled elements")
+
+
+# ---- input check: counts are integers, so the comparison with the oracle is exact ---------------------------------
+@pytest.mark.parametrize("dtype,d_m", [("f32", 64), ("f16", 512), ("bf16", 1024)])
+def test_check_inputs_counts_match_the_oracle(dtype, d_m):
+    import torch
+    import oracle
+    from paper_2105_04779_amd import el_attn
+    g = np.random.default_rng(31)
+    B, n = 5, 77
+    H = wl.round_to_storage(g.standard_normal((B, n, d_m), dtype=np.float32), dtype)
+    lens = np.array([77, 33, 1, 0, 90], dtype=np.int32)          # two of them outside [1, n]
+    # plant special values everywhere, valid rows and padding alike
+    for _ in range(60):
+        b, t, c = int(g.integers(B)), int(g.integers(n)), int(g.integers(d_m))
+        H[b, t, c] = [np.nan, np.inf, -np.inf, 70000.0, -1.0e6, 65504.0, 65536.0][int(g.integers(7))]
+    if dtype == "f16":
+        H = np.where(np.abs(H) > 65504.0, np.sign(H) * np.inf, H).astype(np.float32)   # what fp16 storage would hold
+    H = wl.round_to_storage(H, dtype) if dtype != "f16" else H
+    ref = oracle.check_inputs_reference(H, lens)
+    got = el_attn.check_inputs(to_device(H, dtype), torch.from_numpy(lens).cuda())
+    torch.cuda.synchronize()
+    assert got.cpu().tolist() == ref
+    assert ref[0] == 2 and ref[1] > 0 and (dtype == "f16" or ref[2] > 0)
+    # NULL lengths: every row of every element
+    ref_all = oracle.check_inputs_reference(H, None)
+    got_all = el_attn.check_inputs(to_device(H, dtype), None)
+    torch.cuda.synchronize()
+    assert got_all.cpu().tolist() == ref_all and ref_all[3] == B * n * d_m
+    # a second call into the same report starts from zero again
+    rep = el_attn.check_inputs(to_device(H, dtype), torch.from_numpy(lens).cuda(), report=got_all)
+    torch.cuda.synchronize()
+    assert rep.cpu().tolist() == ref
+
+
+def test_check_inputs_on_a_clean_full_size_batch():
+    import torch
+    from paper_2105_04779_amd import el_attn
+    w = wl.WORKLOADS["c3_bart_large_bf16"]
+    L = wl.lengths(w)
+    H = torch.randn((w.B, w.n, w.d_m), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    H[:, -1, :] = float("nan")                                   # padding of every element shorter than n
+    full = int((L == w.n).sum())
+    got = el_attn.check_inputs(H, torch.from_numpy(L).cuda()).cpu().tolist()
+    assert got == [0, full * w.d_m, 0, int(L.sum()) * w.d_m]
