@@ -145,16 +145,18 @@ k_core_ds(const CoreArgs a)
     // that does not exist (at or beyond len, or of a tile past this workgroup's range) is replaced by a
     // fetch of the element's first row into a dump area.  The fetch counter then advances by exactly NI
     // per tile, and the loop needs neither branches around the requests nor per-tile wait arithmetic.
-    auto issue_dma_row = [&](int kt, int slot, int i) {
+    auto issue_dma_row = [&](int kt, int slot, int i, auto nt_tag) {
+        constexpr bool NT = decltype(nt_tag)::value;
         const bool ok = kt < k1 && kt * kTileRows16 + 4 * w + i < len;               // wave-uniform
         const char *sbase = ok ? Hb + ((size_t)kt * kTileRows16 + 4 * w) * ROWB : Hb - i * ROWB;
         const int f = (i << 2) | w;                                                   // tile_swizzle(4w + i)
         const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
         const unsigned dst = ok ? t_lds + slot * SLOT + (4 * w + i) * ROWB : dz_lds;
-        if (PIECES == 2) dma_row_2k(dst, voff, sbase);
-        else dma_piece(dst, voff, sbase);
+        if (PIECES == 2) { if (NT) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
+        else { if (NT) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
     };
-    auto issue_dma = [&](int kt, int slot) {
+    auto issue_dma_t = [&](int kt, int slot, auto nt_tag) {
+        constexpr bool NT = decltype(nt_tag)::value;
         if (kt < k1 && (kt + 1) * kTileRows16 <= len) {
             // the common case, a whole tile inside the range: one source base and four destinations,
             // without the per-row selects below
@@ -164,13 +166,19 @@ k_core_ds(const CoreArgs a)
             for (int i = 0; i < 4; ++i) {
                 const int f = (i << 2) | w;
                 const unsigned voff = (unsigned)(((l ^ f) << 4) + i * ROWB);
-                if (PIECES == 2) dma_row_2k(dst0 + i * ROWB, voff, sbase);
-                else dma_piece(dst0 + i * ROWB, voff, sbase);
+                if (PIECES == 2) { if (NT) dma_row_2k_nt(dst0 + i * ROWB, voff, sbase); else dma_row_2k(dst0 + i * ROWB, voff, sbase); }
+                else { if (NT) dma_piece_nt(dst0 + i * ROWB, voff, sbase); else dma_piece(dst0 + i * ROWB, voff, sbase); }
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) issue_dma_row(kt, slot, i);
+            for (int i = 0; i < 4; ++i) issue_dma_row(kt, slot, i, nt_tag);
         }
+    };
+    // the cache hint is a launch-wide choice: both forms issue the same number of requests
+    const bool stream_hint = a.stream_hint != 0;
+    auto issue_dma = [&](int kt, int slot) {
+        if (stream_hint) issue_dma_t(kt, slot, std::true_type{});
+        else issue_dma_t(kt, slot, std::false_type{});
     };
     // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
     auto wait_own = [&](int later_tiles) {

@@ -46,6 +46,20 @@ __device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, con
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
 }
 
+// The same requests with the non-temporal hint: the lines are not kept in L2 or in the memory-side cache.
+// For a stream far larger than that cache this leaves it to the data that IS re-read (weights, expanded
+// queries, partial results) and raises the streaming rate itself.
+__device__ __forceinline__ void dma_piece_nt(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma_row_2k_nt(unsigned lds_addr, unsigned voff, const char *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024 nt"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
 static inline size_t dtype_size(int dt) { return dt == EL_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -144,6 +158,7 @@ struct CoreArgs {
     f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
     float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
     int n, B, R, Rs, S, nblocks;
+    int stream_hint;         // nonzero: fetch H with the non-temporal hint (H far larger than the memory-side cache)
 };
 hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 struct CorePlan {
