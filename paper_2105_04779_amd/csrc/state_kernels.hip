@@ -88,15 +88,15 @@ k_check_inputs(const char *__restrict__ H, int64_t stride_b, const int32_t *__re
     };
     auto chunk = [&](const u4v v) { word(v.x); word(v.y); word(v.z); word(v.w); };
     int c = threadIdx.x;
-    // eight independent loads in flight per lane
+    // eight independent loads in flight per lane, non-temporal: the rows are read once
     for (; c + 7 * 256 < chunks; c += 8 * 256) {
         u4v v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = s[c + k * 256];
+        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(s + c + k * 256);
 #pragma unroll
         for (int k = 0; k < 8; ++k) chunk(v[k]);
     }
-    for (; c < chunks; c += 256) chunk(s[c]);
+    for (; c < chunks; c += 256) chunk(__builtin_nontemporal_load(s + c));
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         nonfinite += __shfl_xor(nonfinite, o, 64);
