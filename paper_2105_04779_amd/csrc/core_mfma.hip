@@ -132,10 +132,10 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
     a.elq = (const f16_t *)ws.ELQ; a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.S = pl.S; a.nblocks = pl.nblocks;
-    // H is read once per step; when a batch of it is far larger than the 256 MB memory-side cache, keeping its
+    // H is read once per step; when a batch of it is large against the 256 MB memory-side cache, keeping its
     // lines out of the caches leaves them to the data that is re-read and raises the streaming rate (measured:
-    // 5.3 -> 6.2 TB/s on 1 GB of per-beam histories; neutral below ~300 MB, slower on a 25 MB batch)
-    a.stream_hint = (double)p.B * p.n * p.d_m * 2.0 > 256.0 * 1024 * 1024 ? 1 : 0;
+    // 5.3 -> 6.2 TB/s on 1 GB of per-beam histories; 0.5 us per step at 128 MB; slower on a 25 MB batch)
+    a.stream_hint = (double)p.B * p.n * p.d_m * 2.0 >= 128.0 * 1024 * 1024 ? 1 : 0;
     const bool bf = p.dtype == EL_BF16;
     return launch_core_ds(a, p.d_m, bf, pl.nrg, s, ev0, ev1);
 }
