@@ -78,6 +78,15 @@ def test_small_cases_generic_kernels(dtype, B, beam, heads, d_m, d_k, n, lens):
     run_case(w, lens=lens, flags=el_attn.EL_FLAG_FORCE_GENERIC)
 
 
+# ---- many query rows (several row blocks of every projection kernel, last one ragged) ----------------------
+@pytest.mark.parametrize("dtype,B,beam,heads,d_m,n", [("bf16", 130, 4, 16, 1024, 40), ("f16", 150, 4, 8, 512, 33),
+                                                      ("bf16", 513, 1, 16, 1024, 20)])
+def test_many_rows_not_a_multiple_of_the_tile(dtype, B, beam, heads, d_m, n):
+    w = wl.custom(f"rows_{dtype}_{B}x{beam}", dtype=dtype, B=B, beam=beam, heads=heads, d_m=d_m, d_k=64, n=n,
+                  len_lo=1, len_hi=n, index=59)
+    run_case(w)
+
+
 # ---- degenerate cases ----------------------------------------------------------------------------------------
 def test_single_position_and_single_row():
     w = wl.custom("n1", dtype="bf16", B=2, beam=1, heads=16, d_m=1024, d_k=64, n=1, index=52)
