@@ -168,7 +168,8 @@ el_status el_attn_decode_step(el_attn_ctx *ctx,
  * which equals multi-head attention over the union of the segments' keys.  The
  * segments may come from calls with different (B, beam) factorizations of the
  * same B*beam rows: a shared prefix as (B, beam) and a per-beam suffix as
- * (B*beam, 1) (section 3.1.1).  A segment whose lse is -inf is ignored.  seg_A and
+ * (B*beam, 1) (section 3.1.1; the context must then have been prepared with
+ * max_batch >= B*beam).  A segment whose lse is -inf is ignored.  seg_A and
  * seg_lse passed to merge are HOST arrays of nseg device pointers, read during
  * the call only.  Other arguments as for el_attn_decode_step.  Both calls use the
  * bound workspace and never allocate.
