@@ -18,7 +18,7 @@ bool valid_dtype(int dt) { return dt == EL_F32 || dt == EL_F16 || dt == EL_BF16;
 int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 struct WsLayout {
-    size_t off_Qp, off_ELQ, off_Xp, off_ML, off_Xn, off_A, total;
+    size_t off_Qp, off_ELQ, off_Xp, off_ML, off_Xn, off_A, off_E, total;
 };
 
 WsLayout ws_layout(const el_attn_ctx *c, int B, int beam)
@@ -36,6 +36,7 @@ WsLayout ws_layout(const el_attn_ctx *c, int B, int beam)
     L.off_ML = o;  o = align_up(o + mb * kMaxParts * Rp * 2 * sizeof(float), 256);
     L.off_Xn = o;  o = align_up(o + mb * Rp * d_m * sizeof(float), 256);
     L.off_A = o;   o = align_up(o + mb * mx * hd * sizeof(float), 256);
+    L.off_E = o;   o = align_up(o + (mb + 1) * sizeof(int32_t), 256);
     L.total = o;
     return L;
 }
@@ -51,6 +52,7 @@ Workspace carve(const el_attn_ctx *c)
     w.ML = (float *)(base + L.off_ML);
     w.Xn = (float *)(base + L.off_Xn);
     w.A = (float *)(base + L.off_A);
+    w.E = (int32_t *)(base + L.off_E);
     return w;
 }
 
@@ -100,7 +102,8 @@ Problem make_problem(const el_attn_ctx *ctx, const void *H, int64_t stride, cons
 // the head outputs A (without b^V), in the formats `fmt` names.
 struct StepFormats {
     bool a_f16, qp_f16;     // element type of A and of the projected queries in the workspace
-    int parts, Rstride;     // shape of the key-range statistics [B, parts, Rstride, 2]
+    PieceMap pm;            // which slots of the statistics [slot, Rstride, 2] belong to a batch element
+    int Rstride;
     float ml_to_nat;        // ln 2 where the statistics' maxima are in log2 units
     float c_to_nat;         // ln 2 where the projected queries carry log2(e)
 };
@@ -109,8 +112,9 @@ el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, 
 {
     constexpr float kLn2 = 0.6931471805599453f;
     if (el_attn_uses_mfma(ctx)) {
-        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus);
-        fmt->parts = pl.parts; fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus,
+                                           ctx->cfg.max_batch * kMaxParts);
+        fmt->pm = piece_map(pl, ws, p.B); fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
         // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
         const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
         if (ctx->use_mfma_gemm) {
@@ -136,7 +140,8 @@ el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, 
         if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
         if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
         const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
-        fmt->parts = parts; fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
+        fmt->pm.E = nullptr; fmt->pm.parts = parts; fmt->pm.G = 0; fmt->pm.lfloor = 0; fmt->pm.B = p.B;
+        fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
         const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
         if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;
         if (launch_core_generic(ctx, p, ws, parts, s) != hipSuccess) return EL_ERR_HIP;
@@ -286,23 +291,23 @@ el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits)
 
 el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups)
 {
-    if (!ctx || (row_groups != 0 && row_groups != 1 && row_groups != 2 && row_groups != 4)) return EL_ERR_INVALID_ARG;
+    if (!ctx || (row_groups != 0 && row_groups != 1 && row_groups != 2)) return EL_ERR_INVALID_ARG;
     ctx->nrg_override = row_groups;
     return EL_OK;
 }
 
 el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,
-                               int32_t compute_units, int32_t *row_groups, int32_t *splits)
+                               int32_t compute_units, int32_t *row_groups, int32_t *spans)
 {
-    if (!row_groups || !splits) return EL_ERR_INVALID_ARG;
+    if (!row_groups || !spans) return EL_ERR_INVALID_ARG;
     if (B < 1 || beam < 1 || heads < 1 || n < 1 || compute_units < 1) return EL_ERR_INVALID_ARG;
     if (d_model != 512 && d_model != 1024) return EL_ERR_UNSUPPORTED;
     Problem p;
     std::memset(&p, 0, sizeof(p));
     p.B = B; p.beam = beam; p.n = n; p.heads = heads; p.d_m = d_model; p.R = heads * beam;
-    const CorePlan pl = plan_core_mfma(p, 0, 0, compute_units);
+    const CorePlan pl = plan_core_mfma(p, 0, 0, compute_units, B * kMaxParts);
     *row_groups = pl.nrg;
-    *splits = pl.S;
+    *spans = pl.G;
     return EL_OK;
 }
 
@@ -361,7 +366,7 @@ el_status el_attn_decode_segment(el_attn_ctx *ctx, const void *H, int64_t H_batc
     SegFinishArgs f;
     f.A = ws.A; f.Qp = ws.Qp; f.ML = ws.ML; f.bk32 = ctx->w.bk32; f.bv32 = ctx->w.bv32;
     f.seg_A = seg_A; f.seg_lse = seg_lse;
-    f.beam = beam; f.heads = p.heads; f.d_k = p.d_k; f.hd = p.hd; f.parts = fmt.parts; f.Rstride = fmt.Rstride;
+    f.beam = beam; f.heads = p.heads; f.d_k = p.d_k; f.hd = p.hd; f.pm = fmt.pm; f.Rstride = fmt.Rstride;
     f.ml_to_nat = fmt.ml_to_nat; f.c_to_nat = fmt.c_to_nat;
     if (launch_seg_finish(f, fmt.a_f16, fmt.qp_f16, B * beam, s) != hipSuccess) return EL_ERR_HIP;
     return EL_OK;

@@ -25,6 +25,21 @@ __device__ __forceinline__ void from_f32(float x, bf16_t *p) {
     p->bits = (uint16_t)(u >> 16);
 }
 
+// x = high + low, both in the 16-bit storage type (the pair carries ~16 mantissa bits of x)
+template <bool BF16>
+__device__ __forceinline__ void split16(float x, uint16_t &hi, uint16_t &lo)
+{
+    if (BF16) {
+        bf16_t h, l2;
+        from_f32(x, &h);
+        from_f32(x - to_f32(h), &l2);
+        hi = h.bits; lo = l2.bits;
+    } else {
+        const f16_t h = (f16_t)x, l2 = (f16_t)(x - (float)h);
+        hi = __builtin_bit_cast(uint16_t, h); lo = __builtin_bit_cast(uint16_t, l2);
+    }
+}
+
 // ---- LDS staging helpers shared by the MFMA kernels ---------------------------------------
 // 16-byte chunk swizzle inside a tile row: a bijection of the low four chunk bits that makes both
 // the row-wise b128 reads and the transposing b64 reads spread over all LDS banks.
@@ -38,12 +53,12 @@ __device__ __forceinline__ int row_swizzle(int row) { return ((row & 7) << 1) | 
 __device__ __forceinline__ void dma_piece(unsigned lds_addr, unsigned voff, const char *sbase)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, const char *sbase)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
 // The same requests with the non-temporal hint: the lines are not kept in L2 or in the memory-side cache.
@@ -52,12 +67,12 @@ __device__ __forceinline__ void dma_row_2k(unsigned lds_addr, unsigned voff, con
 __device__ __forceinline__ void dma_piece_nt(unsigned lds_addr, unsigned voff, const char *sbase)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_row_2k_nt(unsigned lds_addr, unsigned voff, const char *sbase)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\tglobal_load_lds_dwordx4 %1, %2 offset:1024 nt"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
 static inline size_t dtype_size(int dt) { return dt == EL_F32 ? 4 : 2; }
@@ -66,6 +81,29 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 // ---- compile-time limits -----------------------------------------------------------------
 constexpr int kMaxParts = 8;        // key-range partials per (batch element, row) the workspace holds
 constexpr int kGenericMaxDm = 8192; // widest d_model the generic core kernel covers
+constexpr int kScanMax = 1024;      // most batch elements whose tiles the streaming core cuts as one list
+
+// Where the partial results ("pieces") of batch element b live: `np` consecutive slots from `slot0` in the
+// partial buffers Xp [slot, Rs, d_m] and ML [slot, Rs, 2].
+//   fixed cut      every element is cut into `parts` key ranges: slots b*parts .. b*parts+parts-1;
+//   flattened cut  the 16-row tiles of all elements form one list, cut into G spans of
+//                  lspan = max(ceil(total / G), lfloor) tiles; the piece of (span g, element b) is slot g + b
+//                  (unique: along the list, span and element never decrease and one of them grows from piece
+//                  to piece).  E [B+1] is the prefix sum of the elements' tile counts, written by the core.
+struct PieceMap {
+    const int32_t *E;       // null: fixed cut
+    int parts;              // fixed cut: parts per element
+    int G, lfloor, B;       // flattened cut
+};
+__device__ __forceinline__ void piece_range(const PieceMap &m, int b, int &slot0, int &np)
+{
+    if (!m.E) { slot0 = b * m.parts; np = m.parts; return; }
+    const int total = m.E[m.B];
+    int lspan = (total + m.G - 1) / m.G;
+    lspan = lspan > m.lfloor ? lspan : m.lfloor;
+    const int g_lo = m.E[b] / lspan, g_hi = (m.E[b + 1] - 1) / lspan;
+    slot0 = g_lo + b; np = g_hi - g_lo + 1;
+}
 
 // ---- problem description handed to the launchers ------------------------------------------
 struct Problem {
@@ -86,6 +124,7 @@ struct Workspace {
     float *ML;      // [B, parts, Rpad, 2]          running max and sum of each partial
     float *Xn;      // [B, R, d_m]                  merged, normalised weighted sums (generic path)
     float *A;       // [B*beam, hd]                 a6 result: fp32 (generic) or fp16 (MFMA GEMMs)
+    int32_t *E;     // [B+1]                        prefix sum of tile counts (flattened cut of the MFMA core)
 };
 
 struct Weights {    // library-owned copies in the storage dtype
@@ -133,10 +172,11 @@ hipError_t launch_vec_f32(int dtype, const void *src, float *dst, int n, hipStre
 struct SegFinishArgs {
     const void *A;            // [rows, hd] fp16 or fp32: the segment's normalised head outputs without b^V
     const void *Qp;           // [rows, hd] fp16 or fp32: projected queries as a1 left them (scaled)
-    const float *ML;          // [B, parts, Rstride, 2] key-range statistics
+    const float *ML;          // [slot, Rstride, 2] statistics of the pieces (see PieceMap)
+    PieceMap pm;
     const float *bk32, *bv32;
     float *seg_A, *seg_lse;
-    int beam, heads, d_k, hd, parts, Rstride;
+    int beam, heads, d_k, hd, Rstride;
     float ml_to_nat, c_to_nat; // factors that turn ML's maxima / the key-bias dot product into natural-log units
 };
 constexpr int kMaxSegments = 4;
@@ -149,27 +189,35 @@ struct SegMergeArgs {
 hipError_t launch_seg_finish(const SegFinishArgs &a, bool a_f16, bool qp_f16, int rows, hipStream_t s);
 hipError_t launch_seg_merge(const SegMergeArgs &a, bool out_f16, int rows, hipStream_t s);
 
-// MFMA attention core -- core_ds.hip (column-split kernel), core_mfma.hip (planning, launch, helpers)
-struct CoreArgs {
+// MFMA attention core -- core_stream.hip (the kernel), core_mfma.hip (planning, launch, helpers)
+struct CorePlan {
+    int nrg;      // 16-row groups per workgroup (1 or 2)
+    int nblocks;  // row blocks (workgroups sharing one H range)
+    int Rs;       // padded row count of ELQ / partial buffers = nblocks * 16 * nrg
+    int flat;     // 1: the tiles of all elements are cut as one list into G spans; 0: one workgroup per (element, row block)
+    int G;        // spans (flat) or batch elements (not flat)
+    int lfloor;   // flat: floor on the span length in tiles, so that no element has more than kMaxParts pieces
+    int parts;    // most pieces per (batch element, row)
+    int slots;    // piece slots the partial buffers must hold
+};
+// Arguments of the streaming core (core_stream.hip)
+struct StreamArgs {
     const void *H;
     int64_t h_stride;        // elements between batch elements
     const int32_t *lengths;
-    const f16_t *elq;        // [B, Rs, DM] fp16, scaled by log2(e)/sqrt(d_k), pad rows zero
-    f16_t *Xp;               // [B, parts, Rs, DM] fp16, each partial already divided by its own sum
-    float *ML;               // [B, parts, Rs, 2]  (reference max in log2 units, sum)
-    int n, B, R, Rs, S, nblocks;
+    const uint16_t *elq_hi;  // [B, Rs, DM] high and low 16-bit planes of EL-Q in the storage type,
+    const uint16_t *elq_lo;  //   scaled by log2(e)/sqrt(d_k)
+    f16_t *Xp;               // [slot, Rs, DM] fp16, each piece already divided by its own sum
+    float *ML;               // [slot, Rs, 2]  (reference max in log2 units, sum)
+    int32_t *E;              // [B+1] prefix sum of tile counts (flat cut), written by the kernel; may be null
+    int n, B, R, Rs, nblocks;
+    int flat, G, lfloor;
     int stream_hint;         // nonzero: fetch H with the non-temporal hint (H far larger than the memory-side cache)
 };
-hipError_t launch_core_ds(const CoreArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
-struct CorePlan {
-    int nrg;      // 16-row groups per workgroup (1, 2 or 4)
-    int nblocks;  // row blocks (workgroups sharing one H range)
-    int Rs;       // padded row count of ELQ / partial buffers = nblocks * 16 * nrg
-    int S;        // contiguous key-range splits per batch element
-    int parts;    // partial results per (batch element, row) = S
-};
+hipError_t launch_core_stream(const StreamArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 bool core_mfma_supported(int dtype, int d_m);
-CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus);
+CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus, int max_slots);
+PieceMap piece_map(const CorePlan &pl, const Workspace &ws, int B);
 hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s);
 hipError_t launch_core_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const CorePlan &pl, hipStream_t s,
                             hipEvent_t ev0, hipEvent_t ev1);   // events, if given, bracket the kernel itself

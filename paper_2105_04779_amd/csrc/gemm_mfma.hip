@@ -5,7 +5,8 @@
 //
 //   a1  Qp    = (q . W^Q + b^Q) * scale   k_gemm_slab  A = queries (storage dtype), Bt = (W^Q)^T (storage dtype)
 //   a2  ELQ_i = Qp_i . (W_i^K)^T          k_elq_slab   A = Qp (fp16),               Bt = W^K in fp16     per head
-//   a6  A_i   = X_i . W_i^V               k_vproj_slab A = merge of split partials, Bt = (W^V)^T in fp16 per head
+//                                                      (result as a high + low pair of planes in the storage type)
+//   a6  A_i   = X_i . W_i^V               k_vproj_slab A = merge of the pieces,     Bt = (W^V)^T in fp16 per head
 //   a7  out   = A . W^O + c_out           k_gemm_slab  A = A (fp16),                Bt = (W^O)^T in fp16
 //
 // Storage-dtype operands enter the MFMA exactly (a1 runs in the storage type).  From a2 on everything
@@ -40,8 +41,11 @@ struct GemmArgs {
     int lda, ldb, ldc;    // row strides in elements
     int x;                // beam: logical row m = b*x + j
     int c_rB;             // k_elq_slab: output row of logical row m, head i = (m / x) * c_rB + i * x + m % x
-    // k_vproj_slab: A points at the normalised fp16 split partials Xp [B, parts, Rs, d_m]; ML [B, parts, Rs, 2]
+    void *C2;             // k_elq_slab: the low plane
+    // k_vproj_slab: A points at the normalised fp16 pieces Xp [slot, Rs, d_m]; ML [slot, Rs, 2]; pm says which
+    // slots belong to a batch element, parts bounds their number
     const float *ML;
+    PieceMap pm;
     int parts, Rs;
 };
 
@@ -193,19 +197,28 @@ k_vproj_slab(const GemmArgs g)
     // per lane), then all partial rows (four rows x the slots in use x both halves), so the whole merge
     // costs one round trip to memory.
     constexpr int HF = ROWB / 1024;
+    int slot0[4], np[4];                                 // pieces of the four rows' batch elements (wave-uniform)
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) {
+        const int m = min(m0 + 4 * w + ii, g.M - 1);
+        piece_range(g.pm, m / g.x, slot0[ii], np[ii]);
+        np[ii] = min(np[ii], kMaxParts);
+    }
     auto row_src = [&](int ii, int p, int hf) {
         const int m = min(m0 + 4 * w + ii, g.M - 1);
-        const int b = m / g.x, r = head * g.x + (m % g.x);
-        return (const h8 *)((const f16_t *)g.A + (((size_t)b * g.parts + p) * g.Rs + r) * g.lda + hf * 512 + 8 * l);
+        const int r = head * g.x + (m % g.x);
+        return (const h8 *)((const f16_t *)g.A + (((size_t)slot0[ii] + p) * g.Rs + r) * g.lda + hf * 512 + 8 * l);
     };
     float mp, lp;
     {
         const int ii = l >> 4, p = l & 15;
         const int m = min(m0 + 4 * w + ii, g.M - 1);
-        const int b = m / g.x, r = head * g.x + (m % g.x);
-        const float *ml = g.ML + (((size_t)b * g.parts + min(p, g.parts - 1)) * g.Rs + r) * 2;
+        const int r = head * g.x + (m % g.x);
+        const int s0 = ii == 0 ? slot0[0] : (ii == 1 ? slot0[1] : (ii == 2 ? slot0[2] : slot0[3]));
+        const int n0 = ii == 0 ? np[0] : (ii == 1 ? np[1] : (ii == 2 ? np[2] : np[3]));
+        const float *ml = g.ML + (((size_t)s0 + min(p, n0 - 1)) * g.Rs + r) * 2;
         mp = ml[0]; lp = ml[1];
-        if (p >= g.parts) lp = 0.f;
+        if (p >= n0) lp = 0.f;
     }
 
     h8 xv[4][HF][kMaxParts];
@@ -213,10 +226,12 @@ k_vproj_slab(const GemmArgs g)
     for (int pp = 0; pp < kMaxParts; ++pp) {
         if (pp >= g.parts) continue;                     // uniform
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
+        for (int ii = 0; ii < 4; ++ii) {
+            if (pp >= np[ii]) continue;                  // uniform
 #pragma unroll
             for (int hf = 0; hf < HF; ++hf)
                 xv[ii][hf][pp] = *row_src(ii, pp, hf);
+        }
     }
     float wgt_lane;
     {
@@ -237,7 +252,7 @@ k_vproj_slab(const GemmArgs g)
 #pragma unroll
         for (int pp = 0; pp < kMaxParts; ++pp) {
             wrow[pp] = __shfl(wgt_lane, 16 * ii + pp, 64);
-            if (pp >= g.parts) wrow[pp] = 0.f;
+            if (pp >= np[ii]) wrow[pp] = 0.f;
         }
 #pragma unroll
         for (int hf = 0; hf < HF; ++hf) {
@@ -341,15 +356,16 @@ hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hi
 // wavefronts walk over the row tiles, so W^K is read once per 256 rows instead of once per 16.
 // Weights are the MFMA's A operand: a lane ends up with four consecutive columns of one row; the
 // 16 x 64 tile then goes through LDS and leaves as whole 128-byte lines.
+template <bool BF>
 __global__ void __launch_bounds__(256)
 k_elq_slab(const GemmArgs g)
 {
-    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    typedef uint16_t q4 __attribute__((ext_vector_type(4)));
     constexpr int MT = 4;                               // row tiles per wavefront
-    __shared__ __attribute__((aligned(16))) _Float16 Ct[4][MT][16 * 72];   // rows 144 bytes apart
+    __shared__ __attribute__((aligned(16))) uint16_t Ct[2][4][MT][16 * 72];   // [plane]; rows 144 bytes apart
 
     const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int r16 = l & 15, q4 = l >> 4;
+    const int r16 = l & 15, qd = l >> 4;
     const int n0 = blockIdx.x * 64, head = blockIdx.y;
     const int mt0 = blockIdx.z * (4 * MT);              // first 16-row tile of this workgroup
 
@@ -358,13 +374,13 @@ k_elq_slab(const GemmArgs g)
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            bfr[t][u] = *(const u4 *)((const f16_t *)g.Bt + (size_t)(n0 + 16 * t + r16) * g.ldb + head * 64 + 32 * u + 8 * q4);
+            bfr[t][u] = *(const u4 *)((const f16_t *)g.Bt + (size_t)(n0 + 16 * t + r16) * g.ldb + head * 64 + 32 * u + 8 * qd);
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
         const int m = min((mt0 + w + 4 * mi) * 16 + r16, g.M - 1);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            afr[mi][u] = *(const u4 *)((const f16_t *)g.A + (size_t)m * g.lda + head * 64 + 32 * u + 8 * q4);
+            afr[mi][u] = *(const u4 *)((const f16_t *)g.A + (size_t)m * g.lda + head * 64 + 32 * u + 8 * qd);
     }
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
@@ -374,7 +390,15 @@ k_elq_slab(const GemmArgs g)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, bfr[t][u]), __builtin_bit_cast(h8, afr[mi][u]), acc, 0, 0, 0);
-            *(h4 *)(&Ct[w][mi][r16 * 72 + 16 * t + 4 * q4]) = h4{(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
+            q4 hi, lo;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint16_t h, l2;
+                split16<BF>(acc[e], h, l2);
+                hi[e] = h; lo[e] = l2;
+            }
+            *(q4 *)(&Ct[0][w][mi][r16 * 72 + 16 * t + 4 * qd]) = hi;
+            *(q4 *)(&Ct[1][w][mi][r16 * 72 + 16 * t + 4 * qd]) = lo;
         }
     }
     // a wavefront reads back only what it wrote: no barrier.  Eight lanes write one 128-byte row piece.
@@ -385,7 +409,8 @@ k_elq_slab(const GemmArgs g)
             const int row = 8 * hf + (l >> 3), m = (mt0 + w + 4 * mi) * 16 + row;
             if (m >= g.M) continue;
             const size_t c_row = (size_t)(m / g.x) * g.c_rB + (size_t)(m % g.x) + (size_t)head * g.x;
-            *(h8 *)((f16_t *)g.C + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const h8 *)(&Ct[w][mi][row * 72 + 8 * (l & 7)]);
+            *(u4 *)((uint16_t *)g.C + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const u4 *)(&Ct[0][w][mi][row * 72 + 8 * (l & 7)]);
+            *(u4 *)((uint16_t *)g.C2 + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const u4 *)(&Ct[1][w][mi][row * 72 + 8 * (l & 7)]);
         }
     }
 }
@@ -424,10 +449,12 @@ hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s)
 {
     GemmArgs g = base_args(p);
-    g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ;
+    g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ; g.C2 = (uint16_t *)ws.ELQ + (size_t)p.B * Rs * p.d_m;
     g.N = p.d_m; g.K = p.d_k; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
     g.c_rB = Rs;
-    hipLaunchKernelGGL(k_elq_slab, dim3(p.d_m / 64, p.heads, (g.M + 255) / 256), dim3(256), 0, s, g);
+    const dim3 grid(p.d_m / 64, p.heads, (g.M + 255) / 256);
+    if (p.dtype == EL_BF16) hipLaunchKernelGGL(k_elq_slab<true>, grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(k_elq_slab<false>, grid, dim3(256), 0, s, g);
     return hipGetLastError();
 }
 
@@ -437,6 +464,7 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
 {
     GemmArgs g = base_args(p);
     g.A = ws.Xp; g.Bt = ctx->w.WvT; g.C = ws.A; g.ML = ws.ML; g.parts = pl.parts; g.Rs = pl.Rs;
+    g.pm = piece_map(pl, ws, p.B);
     g.N = p.d_k; g.K = p.d_m; g.lda = p.d_m; g.ldb = p.d_m; g.ldc = p.hd;
     const dim3 grid((g.M + 15) / 16, p.heads), block(256);
     if (p.d_m == 1024) hipLaunchKernelGGL((k_vproj_slab<1024>), grid, block, 0, s, g);

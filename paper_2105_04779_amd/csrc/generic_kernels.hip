@@ -338,14 +338,16 @@ __global__ void k_seg_finish(const SegFinishArgs a)
     a.seg_A[(size_t)m * a.hd + cg] = to_f32(((const TA *)a.A)[(size_t)m * a.hd + cg]) + a.bv32[cg];
     if (cg % a.d_k != 0) return;
     const int i = cg / a.d_k, b = m / a.beam, j = m % a.beam, r = i * a.beam + j;
+    int slot0, np;
+    piece_range(a.pm, b, slot0, np);
     float M = -INFINITY;
-    for (int p = 0; p < a.parts; ++p) {
-        const float *ml = a.ML + (((size_t)b * a.parts + p) * a.Rstride + r) * 2;
+    for (int p = 0; p < np; ++p) {
+        const float *ml = a.ML + (((size_t)slot0 + p) * a.Rstride + r) * 2;
         if (ml[1] > 0.f) M = fmaxf(M, ml[0]);
     }
     float L = 0.f;
-    for (int p = 0; p < a.parts; ++p) {
-        const float *ml = a.ML + (((size_t)b * a.parts + p) * a.Rstride + r) * 2;
+    for (int p = 0; p < np; ++p) {
+        const float *ml = a.ML + (((size_t)slot0 + p) * a.Rstride + r) * 2;
         if (ml[1] > 0.f) L += expf((ml[0] - M) * a.ml_to_nat) * ml[1];
     }
     float c = 0.f;
