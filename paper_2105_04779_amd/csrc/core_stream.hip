@@ -2,31 +2,31 @@
 // products over the hidden states and the softmax between them; Eq. 9 with K = V = H).
 //
 // The valid 16-row tiles of all batch elements form one list (element 0's tiles, then element 1's,
-// ...).  The list is cut into G equal spans; a workgroup (8 wavefronts, two per SIMD) walks one span
-// for one block of 16 or 32 expanded-query rows, so every compute unit streams the same number of
-// bytes whatever the lengths are.  Where a span crosses from one batch element to the next the
-// workgroup closes a PIECE: it writes that element's partial result (normalised by its own sum,
-// with the softmax statistics) to slot `span + element` and starts the next element with fresh
-// statistics; a6 merges an element's pieces by the log-sum-exp rule.  An element that lies inside
-// one span has one piece and needs no merge.
+// ...).  The list is cut into G equal spans; a workgroup walks one span for one block of 16 or 32
+// expanded-query rows, so every compute unit streams the same number of bytes whatever the lengths
+// are.  Where a span crosses from one batch element to the next the workgroup closes a PIECE: it
+// writes that element's partial result (normalised by its own sum, with the softmax statistics) to
+// slot `span + element` and starts the next element with fresh statistics; a6 merges an element's
+// pieces by the log-sum-exp rule.  An element that lies inside one span has one piece and needs no
+// merge.
 //
-// The eight wavefronts split the MODEL dimension: wavefront w owns columns [w d_m/8, (w+1) d_m/8) of
-// H for both products, so each byte of a tile is read from LDS exactly twice per workgroup.
+// A workgroup is eight wavefronts, two per SIMD, with two roles, so that on every SIMD the LDS
+// traffic and dependent chains of one role hide behind the MFMAs of the other:
 //
-//   fetch      each 1 KB piece of a tile row goes straight from HBM into one of four LDS tile
-//              slots (global_load_lds; two tiles are outstanding while two are in use), across
-//              piece boundaries as well.  Lane i of a 1 KB piece fetches chunk i ^ swizzle(row), which
-//              keeps both operand read patterns spread over all banks.
-//   scores     S^T[t, r] partial over the wave's columns: 16x16x32 MFMA in the STORAGE type,
-//              A = H rows (ds_read_b128), B = the wave's slice of EL-Q (registers).  EL-Q is held
-//              as a high + low pair of 16-bit values (two MFMAs), so the score keeps ~16 mantissa
-//              bits however peaked the softmax is, and bf16 H enters the MFMA as it is.
-//   exchange   the eight partial score tiles meet in LDS; wavefront g < RG sums them for row group
-//              g and does that group's softmax bookkeeping in fp32 (running reference maximum,
-//              advanced only when it would grow by more than 2^10), then publishes P and the
-//              rescale factors.  P is fp16 (fp16 storage) or a high + low bf16 pair (bf16 storage).
-//   weighted   X^T[d, r] += H^T[d, t] P^T[t, r]: 32x32x16 MFMA, A = H columns through the
-//   sum        transposing LDS read (ds_read_b64_tr_b16), B = P from LDS; fp32 accumulators.
+//   score wavefronts (0..3)   own one 16-row group of expanded queries and 1/2 or 1/4 of the model
+//       dimension.  S^T[t, r] partial over those columns: 16x16x32 MFMA in the STORAGE type, A = H rows
+//       (ds_read_b128), B = the wavefront's slice of EL-Q held in registers as a high + low pair of
+//       16-bit values (two MFMAs), so a score keeps ~16 mantissa bits however peaked the softmax
+//       is, and bf16 H enters the MFMA as it is.  The partials of a row group meet in LDS; its first
+//       wavefront sums them and does the softmax bookkeeping in fp32 (running reference maximum,
+//       advanced only when it would grow by more than 2^10), then publishes P (fp16, or a high + low
+//       bf16 pair) and the rescale factors.
+//   sum wavefronts (4..7)     own a quarter of the model dimension: X^T[d, r] += H^T[d, t] P^T[t, r],
+//       32x32x16 MFMA, A = H columns through the transposing LDS read (ds_read_b64_tr_b16), B = P from
+//       LDS, fp32 accumulators.  They also request the tiles: each 1 KB piece of a tile row goes
+//       straight from HBM into one of four LDS tile slots (global_load_lds; two tiles are outstanding
+//       while two are in use), across piece boundaries as well.  Lane i of a 1 KB piece fetches chunk
+//       i ^ swizzle(row), which keeps both operand read patterns spread over all banks.
 //
 // Scores and softmax of a tile run one tile ahead of its weighted sum; two barriers per tile.
 // Scores arrive pre-multiplied by log2(e)/sqrt(d_k), so the softmax is an exp2 of a difference.
@@ -87,22 +87,21 @@ template <int DM, bool BF16, int RG>
 __global__ void __launch_bounds__(512)
 k_core_stream(const StreamArgs a)
 {
-    constexpr int NW = 8;                           // wavefronts per workgroup
     constexpr int ROWB = DM * 2;                    // bytes per tile row (2-byte elements)
     constexpr int SLOT = kTile * ROWB;              // one tile
     constexpr int NSLOT = 4;
     constexpr int PIECES = ROWB / 1024;             // 1 KB LDS-DMA pieces per row
-    constexpr int NI = 2 * PIECES;                  // fetch instructions per wavefront per tile (two rows)
-    constexpr int DS = DM / NW;                     // columns per wavefront
-    constexpr int KC = DS / 32;                     // k-chunks of the score product
-    constexpr int MB = DS / 32;                     // 32-column blocks of the output
+    constexpr int NI = 4 * PIECES;                  // fetch instructions per sum wavefront per tile (four rows)
+    constexpr int PARTS = 4 / RG;                   // score wavefronts per row group (column parts)
+    constexpr int CHK = DM / 32 / PARTS;            // 32-column chunks of one score wavefront
+    constexpr int DS = DM / 4;                      // columns per sum wavefront
+    constexpr int MB = DS / 32;                     // 32-column blocks of the output per sum wavefront
     constexpr int NP = BF16 ? 2 : 1;                // 16-bit planes of P
-    constexpr int CWC = DS * 2 / 16;                // 16-byte chunks in a wavefront's column slice
-    static_assert(ROWB % 1024 == 0 && (KC == 2 || KC == 4), "d_m is 512 or 1024");
+    static_assert(DM == 512 || DM == 1024, "d_m is 512 or 1024");
     static_assert(RG == 1 || RG == 2, "row groups per workgroup");
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
-    __shared__ __attribute__((aligned(16))) float Sx[NW * RG * 64 * 4];       // partial scores [wave][rg][slot][4]
+    __shared__ __attribute__((aligned(16))) float Sx[4 * 64 * 4];             // partial scores [score wave][slot][4]
     __shared__ __attribute__((aligned(16))) uint16_t Px[2 * NP * 32 * 16];    // probabilities [tile parity][plane][row][t]
     __shared__ float Ax[2 * 32];                                              // per-row rescale factor [tile parity][row]
     __shared__ float Linv[32];                                                // per-row 1/sum of the piece being closed
@@ -166,329 +165,318 @@ k_core_stream(const StreamArgs a)
         nspan = (clamp_len(a.lengths ? a.lengths[b0] : a.n) + kTile - 1) / kTile;
     }
     auto elem_len = [&](int b) -> int {
-        if (a.flat) return b < a.B ? Lt[b] : kTile;
-        return clamp_len(a.lengths ? a.lengths[min(b, a.B - 1)] : a.n);
+        int v;
+        if (a.flat) v = b < a.B ? Lt[b] : kTile;
+        else v = clamp_len(a.lengths ? a.lengths[min(b, a.B - 1)] : a.n);
+        return __builtin_amdgcn_readfirstlane(v);
     };
 
     const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
     const unsigned t_lds = (unsigned)(uintptr_t)Tl;
     const unsigned dz_lds = (unsigned)(uintptr_t)(const EL_LDS(char) *)Dz;
-    const bool stream_hint = a.stream_hint != 0;
-
-    // ---- fetch cursor: the tile that is requested next (two list positions ahead of the scores) ----
-    int f_b = b0, f_kt = kt0, f_len = __builtin_amdgcn_readfirstlane(elem_len(b0)), f_pos = 0;
-    const char *f_H = (const char *)a.H + (size_t)b0 * a.h_stride * 2;
-
-    // A wavefront fetches rows 2w, 2w+1 of every tile, always with the same number of instructions: a row
-    // that does not exist (at or beyond the element's length, or past the span) is replaced by a fetch of the
-    // first row of H into a dump area, and, if the tile will be used, zeros are written in its place (the slot
-    // is free when its fetch is requested).  The fetch counter then advances by exactly NI per tile.
-    auto dma = [&](unsigned dst, unsigned voff, const char *sbase) {
-        if (PIECES == 2) { if (stream_hint) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
-        else { if (stream_hint) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
-    };
-    auto fetch_next = [&]() {
-        const int slot = f_pos & 3;
-        const bool live = f_pos < nspan;
-        const int rows = live ? f_len - f_kt * kTile : 0;              // valid rows of this tile (may exceed 16)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int row = 2 * w + i;
-            const bool ok = row < rows;                                    // wave-uniform
-            const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 2 * w) * ROWB : (const char *)a.H - i * ROWB;
-            const unsigned voff = (unsigned)(((l ^ tile_swizzle(row)) << 4) + i * ROWB);
-            const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
-            dma(dst, voff, sbase);
-            if (live && !ok) {
-#pragma unroll
-                for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
-            }
-        }
-        ++f_pos;
-        if (live) {
-            if (++f_kt * kTile >= f_len) {
-                ++f_b; f_kt = 0;
-                f_len = __builtin_amdgcn_readfirstlane(elem_len(f_b));
-                f_H = (const char *)a.H + (size_t)min(f_b, a.B - 1) * a.h_stride * 2;
-            }
-        }
-    };
-    // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
-    auto wait_own = [&](int later_tiles) {
-        if (later_tiles >= 2) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NI) : "memory");
-        else if (later_tiles == 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NI) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    };
-
-    // ---- this wavefront's column slice of EL-Q (high and low planes): B operand of the score product ----
-    u4 elq[RG][KC][2];
-    auto load_elq = [&](int b) {
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg) {
-            const int row = row0 + 16 * rg + r16;
-            const size_t off = ((size_t)b * a.Rs + row) * DM + DS * w + 8 * g;
-#pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                elq[rg][c][0] = elq[rg][c][1] = u4{0u, 0u, 0u, 0u};   // pad rows (>= R) are never written by a2
-                if (row < a.R) {
-                    elq[rg][c][0] = *(const u4 *)(a.elq_hi + off + 32 * c);
-                    elq[rg][c][1] = *(const u4 *)(a.elq_lo + off + 32 * c);
-                }
-            }
-        }
-    };
-    // The compiler does not see the LDS-DMA requests; it does see these loads, and would place their wait (which
-    // also drains every later fetch) in front of the first MFMA of every tile.  Consuming the registers right
-    // after an explicit wait keeps that wait here.
-    auto settle_elq = [&]() {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg)
-#pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                asm volatile("" : "+v"(elq[rg][c][0]));
-                asm volatile("" : "+v"(elq[rg][c][1]));
-            }
-    };
-
-    // ---- prologue: two tiles requested, then the expanded queries ----
-    fetch_next();
-    fetch_next();
-    load_elq(b0);
 
     if (tid < 2 * 32) Ax[tid] = 1.0f;
     for (int i = tid; i < 2 * NP * 32 * 16; i += 512) Px[i] = 0;
 
-    // ---- per-lane LDS offsets inside a tile slot ----
-    int a_base[KC];   // score product: row r16, 16-byte chunk (slice) + 4c + g
-    {
-        const int fx = tile_swizzle(r16);
-#pragma unroll
-        for (int c = 0; c < KC; ++c) a_base[c] = r16 * ROWB + (((CWC * w + 4 * c + g) ^ fx) << 4);
-    }
-    int b_lo[MB], b_hi[MB];   // weighted sum: lane i = 4k+q of 16-lane block (dh, kg) reads row 8kg+k (+4), columns 32mb+16dh+4q..+3
-    {
-        const int dh = g & 1, k = r16 >> 2, q = r16 & 3;
-        const int t_lo = 8 * kg + k, t_hi = t_lo + 4;
-        const int f_lo = tile_swizzle(t_lo), f_hi = tile_swizzle(t_hi);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int cl = CWC * w + 4 * mb + 2 * dh + (q >> 1);
-            b_lo[mb] = t_lo * ROWB + ((cl ^ f_lo) << 4) + (q & 1) * 8;
-            b_hi[mb] = t_hi * ROWB + ((cl ^ f_hi) << 4) + (q & 1) * 8;
-        }
-    }
     // partial scores of lane (row r16, position group g) go to exchange slot 4 r16 + (g ^ (r16 >> 2)): both the
-    // b128 writes here and the owner's b128 reads (lane = 4 row + group) then touch 16 different chunks per 16 lanes
+    // b128 writes and the owner's b128 reads (lane = 4 row + group) then touch 16 different chunks per 16 lanes
     const int sx_put = (4 * r16 + (g ^ (r16 >> 2))) * 4;
     const int sr = l >> 2, sq = l & 3;                                    // softmax lane = 4 * row + position group
     const int sx_get = (4 * sr + (sq ^ (sr >> 2))) * 4;
 
-    f16v X[MB];
+    // What crosses the barriers of tile j (list position):
+    //   B1(j): the partial scores of tile j are in LDS;
+    //   B2(j): P and the rescale factors of tile j are in LDS (buffer j&1; the weighted sum of tile j-1 read the
+    //          other buffer); every sum wavefront has left the weighted sum of tile j-1, so that tile's slot may
+    //          be refilled (tile j+3 goes there, requested after this barrier), and has waited for its own rows
+    //          of tile j+1.
+    // Both roles run the same sequence of barriers: B1, B2 per tile; C1, C2 where a piece is closed.
+    if (w < 4) {
+        // =========================== score wavefront ===========================
+        const int rg = w / PARTS, part = w % PARTS;
+        const bool owner = part == 0;
+        int a_base[CHK];                                 // row r16, 16-byte chunk 4 (part CHK + c) + g of the row
+        {
+            const int fx = tile_swizzle(r16);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
-    float m_ref = -INFINITY, l_sum = 0.f;           // meaningful in owner wavefronts (w < RG) only
-
-    settle_elq();                                   // EL-Q and, requested before it, both tiles
-    __syncthreads();
-
-    // ---- scores of the tile at list position pos (slot pos&3) over this wavefront's columns, left in LDS for
-    //      the exchange; the fetch two positions ahead is requested behind the fragment loads ----
-    auto scores = [&](int pos) {
-        const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
-        u4 hb[KC];
-#pragma unroll
-        for (int c = 0; c < KC; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
-        fetch_next();
-        f4 sc[RG];
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg) sc[rg] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < KC; ++c)
-#pragma unroll
-            for (int rg = 0; rg < RG; ++rg) {
-                sc[rg] = Mma<BF16>::s16(hb[c], elq[rg][c][0], sc[rg]);
-                sc[rg] = Mma<BF16>::s16(hb[c], elq[rg][c][1], sc[rg]);
-            }
-#pragma unroll
-        for (int rg = 0; rg < RG; ++rg) *(f4 *)(Sx + (w * RG + rg) * 256 + sx_put) = sc[rg];
-    };
-
-    // ---- softmax bookkeeping of row group w for one tile, cut into stages that the weighted sum of the
-    //      previous tile interleaves with its MFMAs.  Lane = 4 * row + q holds positions 4q..4q+3 of its
-    //      row, so a row's statistics stay inside a quad.  Everything is branch-free: a row whose maximum
-    //      does not grow gets the factor exp2(0) = 1. ----
-    const bool owner = w < RG;
-    f4 st[NW];
-    float sv[4], pr[4], mx_l = 0.f, alpha = 1.f;
-    auto sm_load = [&]() {
-        if (!owner) return;
-#pragma unroll
-        for (int p = 0; p < NW; ++p) st[p] = *(const f4 *)(Sx + (p * RG + w) * 256 + sx_get);
-    };
-    auto sm_stage1 = [&](int lim_rows) {                              // sum of the partials, local maximum
-        if (!owner) return;
-        const int lim = lim_rows - 4 * sq;                             // positions at or beyond the length do not exist
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            sv[j] = ((st[0][j] + st[1][j]) + (st[2][j] + st[3][j])) + ((st[4][j] + st[5][j]) + (st[6][j] + st[7][j]));
-            sv[j] = j < lim ? sv[j] : -INFINITY;
+            for (int c = 0; c < CHK; ++c) a_base[c] = r16 * ROWB + (((4 * (part * CHK + c) + g) ^ fx) << 4);
         }
-        mx_l = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-    };
-    auto sm_stage2 = [&]() {                                          // row maximum, reference, rescale factor
-        if (!owner) return;
-        float mx = fmaxf(mx_l, quad_xor1(mx_l));
-        mx = fmaxf(mx, quad_xor2(mx));
-        const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
-        // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
-        alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
-        m_ref = m_new;
-    };
-    auto sm_stage3 = [&]() {                                          // probabilities and running sum
-        if (!owner) return;
-        l_sum *= alpha;
+        // this wavefront's slice of EL-Q (high and low planes): B operand of the score product
+        u4 elq[CHK][2];
+        auto load_elq = [&](int b) {
+            const int row = row0 + 16 * rg + r16;
+            const size_t off = ((size_t)b * a.Rs + row) * DM + 32 * (part * CHK) + 8 * g;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
-    };
-    auto sm_stage4 = [&](int buf) {                                   // publish P and the factors
-        if (!owner) return;
-        uint16_t *dst = Px + buf * (NP * 32 * 16) + (16 * w + sr) * 16 + 4 * sq;
-        if (BF16) {
-            // p = high + low, both bf16 by truncation: the pair carries 16 mantissa bits of p
-            unsigned hi[4], lo[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                hi[j] = __float_as_uint(pr[j]) & 0xffff0000u;
-                lo[j] = __float_as_uint(pr[j] - __uint_as_float(hi[j]));
-            }
-            *(u2 *)dst = u2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
-            *(u2 *)(dst + 32 * 16) = u2{(lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u)};
-        } else {
-            const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
-            *(h4 *)dst = h4{p01[0], p01[1], p23[0], p23[1]};
-        }
-        if (sq == 0) Ax[buf * 32 + 16 * w + sr] = alpha;
-    };
-
-    // ---- weighted sum of the tile at list position pos over this wavefront's columns:
-    //      X^T[d, r] += sum_t H[t, d] P[r, t]; with sm, the softmax stages of the next tile ride between its MFMAs ----
-    s4 tb[MB][2];
-    u4 P[NP];
-    float al;
-    auto pv_loads = [&](int pos) {                                    // operands that do not depend on the barrier
-        const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
-        const int buf = pos & 1;
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + (buf * NP + pl) * (32 * 16) + r32 * 16 + 8 * kg);
-        al = Ax[buf * 32 + r32];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb]));
-            tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb]));
-        }
-    };
-    auto pv = [&](bool sm, int lim_rows, int buf_next) {
-        if (sm) sm_load();
-        if (__any(al != 1.0f)) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) X[mb][i] *= al;
-        }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const s4 lo = tb[mb][0], hi = tb[mb][1];
-            const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-#pragma unroll
-            for (int pl = 0; pl < NP; ++pl) X[mb] = Mma<BF16>::s32(hfrag, P[pl], X[mb]);
-            if (sm) {
-                if (mb == 0) sm_stage1(lim_rows);
-                if (mb == 1) { sm_stage2(); if (MB == 2) { sm_stage3(); sm_stage4(buf_next); } }
-                if (MB > 2 && mb == 2) sm_stage3();
-                if (MB > 2 && mb == 3) sm_stage4(buf_next);
-            }
-        }
-    };
-
-    // ---- close a piece: statistics from the owner wavefronts, X normalised by its own sum, straight
-    //      from the accumulators (a lane holds four consecutive columns of one row: 8-byte stores, two lanes
-    //      side by side, four instructions fill 64 bytes of each of 32 rows) ----
-    auto close_piece = [&](int b) {
-        const size_t slot = (size_t)(a.flat ? span + b : b);
-        if (owner) {
-            l_sum += quad_xor1(l_sum);
-            l_sum += quad_xor2(l_sum);
-            const int row = row0 + 16 * w + sr;
-            if (sq == 0) {
-                Linv[16 * w + sr] = l_sum > 0.f ? 1.0f / l_sum : 0.f;
+            for (int c = 0; c < CHK; ++c) {
+                elq[c][0] = elq[c][1] = u4{0u, 0u, 0u, 0u};               // pad rows (>= R) are never written by a2
                 if (row < a.R) {
-                    float *ml_out = a.ML + (slot * a.Rs + row) * 2;
-                    ml_out[0] = m_ref; ml_out[1] = l_sum;
+                    elq[c][0] = *(const u4 *)(a.elq_hi + off + 32 * c);
+                    elq[c][1] = *(const u4 *)(a.elq_lo + off + 32 * c);
                 }
             }
-        }
-        __syncthreads();
-        const float inv = r32 < 16 * RG ? Linv[r32] : 0.f;
-        if (r32 < 16 * RG && row0 + r32 < a.R) {
-            f16_t *x_out = a.Xp + (slot * a.Rs + row0 + r32) * DM + DS * w + 4 * kg;
+        };
+        auto scores = [&](int pos) {
+            const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
+            // the fragment reads run PF chunks ahead of the MFMAs that use them: a read takes ~33 clocks to issue and
+            // ~100 to return, a pair of MFMAs 35, so the chain of MFMAs never waits and the reads issue in its shadow
+            constexpr int PF = CHK < 4 ? CHK : 4;
+            u4 hb[CHK];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
+            f4 sc = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const h2 lo = __builtin_convertvector(f2{X[mb][4 * q4 + 0] * inv, X[mb][4 * q4 + 1] * inv}, h2);
-                    const h2 hi = __builtin_convertvector(f2{X[mb][4 * q4 + 2] * inv, X[mb][4 * q4 + 3] * inv}, h2);
-                    *(h4 *)(x_out + 32 * mb + 8 * q4) = h4{lo[0], lo[1], hi[0], hi[1]};
+            for (int c = 0; c < CHK; ++c) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (c + PF < CHK) hb[c + PF] = *(const EL_LDS(u4) *)(F + a_base[c + PF]);
+                sc = Mma<BF16>::s16(hb[c], elq[c][0], sc);
+                sc = Mma<BF16>::s16(hb[c], elq[c][1], sc);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            *(f4 *)(Sx + w * 256 + sx_put) = sc;
+        };
+        // softmax bookkeeping of this row group for one tile (owner only).  Lane = 4 * row + q holds positions
+        // 4q..4q+3 of its row, so a row's statistics stay inside a quad.  Branch-free: a row whose maximum does
+        // not grow gets the factor exp2(0) = 1.
+        float m_ref = -INFINITY, l_sum = 0.f;
+        auto softmax = [&](int lim_rows, int buf) {
+            if (!owner) return;
+            float sv[4], pr[4];
+            {
+                f4 st[PARTS];
+#pragma unroll
+                for (int p = 0; p < PARTS; ++p) st[p] = *(const f4 *)(Sx + (rg * PARTS + p) * 256 + sx_get);
+                const int lim = lim_rows - 4 * sq;                         // positions at or beyond the length do not exist
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float v = st[0][j];
+#pragma unroll
+                    for (int p = 1; p < PARTS; ++p) v += st[p][j];
+                    sv[j] = j < lim ? v : -INFINITY;
                 }
+            }
+            float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+            mx = fmaxf(mx, quad_xor1(mx));
+            mx = fmaxf(mx, quad_xor2(mx));
+            const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
+            // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
+            const float alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            l_sum *= alpha;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
+            uint16_t *dst = Px + buf * (NP * 32 * 16) + (16 * rg + sr) * 16 + 4 * sq;
+            if (BF16) {
+                // p = high + low, both bf16 by truncation: the pair carries 16 mantissa bits of p
+                unsigned hi[4], lo[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    hi[j] = __float_as_uint(pr[j]) & 0xffff0000u;
+                    lo[j] = __float_as_uint(pr[j] - __uint_as_float(hi[j]));
+                }
+                *(u2 *)dst = u2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
+                *(u2 *)(dst + 32 * 16) = u2{(lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u)};
+            } else {
+                const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
+                *(h4 *)dst = h4{p01[0], p01[1], p23[0], p23[1]};
+            }
+            if (sq == 0) Ax[buf * 32 + 16 * rg + sr] = alpha;
+        };
+
+        load_elq(b0);
+        int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
+        __syncthreads();                                              // S0: the first two tiles have landed
+        for (int j = 0;;) {
+            const int ntile = (c_len + kTile - 1) / kTile;
+            const int npc = min(ntile - c_kt, nspan - j);                // tiles of this piece
+            for (int k = 0; k < npc; ++k) {
+                scores(j + k);
+                __syncthreads();                                      // B1
+                softmax(c_len - (c_kt + k) * kTile, (j + k) & 1);
+                __syncthreads();                                      // B2
+            }
+            j += npc;
+            const bool more = j < nspan;
+            // the next element's expanded queries are requested while the sum wavefronts finish this one
+            if (more) load_elq(c_b + 1);
+            // close the piece: this row group's statistics
+            if (owner) {
+                l_sum += quad_xor1(l_sum);
+                l_sum += quad_xor2(l_sum);
+                const int row = row0 + 16 * rg + sr;
+                if (sq == 0) {
+                    Linv[16 * rg + sr] = l_sum > 0.f ? 1.0f / l_sum : 0.f;
+                    if (row < a.R) {
+                        float *ml_out = a.ML + ((size_t)(a.flat ? span + c_b : c_b) * a.Rs + row) * 2;
+                        ml_out[0] = m_ref; ml_out[1] = l_sum;
+                    }
+                }
+            }
+            m_ref = -INFINITY; l_sum = 0.f;
+            __syncthreads();                                          // C1: 1/sum of every row is in LDS
+            if (!more) break;
+            ++c_b; c_kt = 0; c_len = elem_len(c_b);
+            __syncthreads();                                          // C2: the sum wavefronts are done with the piece
         }
+    } else {
+        // =========================== sum wavefront ===========================
+        const int v = w - 4;
+        const bool stream_hint = a.stream_hint != 0;
+        // fetch cursor: the tile that is requested next (two list positions ahead of the scores)
+        int f_b = b0, f_kt = kt0, f_len = elem_len(b0), f_pos = 0;
+        const char *f_H = (const char *)a.H + (size_t)b0 * a.h_stride * 2;
+        // A sum wavefront fetches rows 4v..4v+3 of every tile, always with the same number of instructions: a
+        // row that does not exist (at or beyond the element's length, or past the span) is replaced by a fetch
+        // of the first row of H into a dump area, and, if the tile will be used, zeros are written in its place
+        // (the slot is free when its fetch is requested).  The fetch counter then advances by exactly NI per tile.
+        auto dma = [&](unsigned dst, unsigned voff, const char *sbase) {
+            if (PIECES == 2) { if (stream_hint) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
+            else { if (stream_hint) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
+        };
+        unsigned voff4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) voff4[i] = (unsigned)(((l ^ ((i << 2) | v)) << 4) + i * ROWB);    // tile_swizzle(4v + i)
+        auto fetch_next = [&]() {
+            const int slot = f_pos & 3;
+            const bool live = f_pos < nspan;
+            const int rows = live ? f_len - f_kt * kTile : 0;          // valid rows of this tile (may exceed 16)
+            if (rows >= kTile) {
+                // the common case, a whole tile: one source base, four destinations, no per-row choices
+                const char *sbase = f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB;
+                const unsigned dst0 = t_lds + slot * SLOT + 4 * v * ROWB;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dma(dst0 + i * ROWB, voff4[i], sbase);
+            } else
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 4 * v + i;
+                const bool ok = row < rows;                                // wave-uniform
+                const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB : (const char *)a.H - i * ROWB;
+                const unsigned voff = (unsigned)(((l ^ ((i << 2) | v)) << 4) + i * ROWB);   // tile_swizzle(4v + i)
+                const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
+                dma(dst, voff, sbase);
+                if (live && !ok) {
+#pragma unroll
+                    for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
+                }
+            }
+            ++f_pos;
+            if (live) {
+                if (++f_kt * kTile >= f_len) {
+                    ++f_b; f_kt = 0;
+                    f_len = elem_len(f_b);
+                    f_H = (const char *)a.H + (size_t)min(f_b, a.B - 1) * a.h_stride * 2;
+                }
+            }
+        };
+        // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
+        auto wait_own = [&](int later_tiles) {
+            if (later_tiles >= 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NI) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        };
+        int b_lo[4], b_hi[4];   // lane i = 4k+q of 16-lane block (dh, kg) reads row 8kg+k (+4), columns 32mb+16dh+4q..+3
+        {
+            const int dh = g & 1, k = r16 >> 2, q = r16 & 3;
+            const int t_lo = 8 * kg + k, t_hi = t_lo + 4;
+            const int f_lo = tile_swizzle(t_lo), f_hi = tile_swizzle(t_hi);
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const int cl = (DS * 2 / 16) * v + 4 * mi + 2 * dh + (q >> 1);
+                b_lo[mi] = t_lo * ROWB + ((cl ^ f_lo) << 4) + (q & 1) * 8;
+                b_hi[mi] = t_hi * ROWB + ((cl ^ f_hi) << 4) + (q & 1) * 8;
+            }
+        }
+        f16v X[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
-        m_ref = -INFINITY; l_sum = 0.f;
-    };
 
-    // What crosses the barriers of tile j (list position):
-    //   B1(j): the partial scores of tile j are in LDS;
-    //   B2(j): P and the rescale factors of tile j are in LDS (buffer j&1; the weighted sum of tile j-1 took its
-    //          operands from the other buffer before B1(j)); every wavefront has left the weighted sum of tile
-    //          j-1, so that tile's slot may be refilled (tile j+3 goes there, requested at the start of the
-    //          scores of tile j+1), and has waited for its own rows of tile j+1.
-    int c_b = b0, c_kt = kt0, c_len = __builtin_amdgcn_readfirstlane(elem_len(b0));
-    for (int j = 0;;) {
-        const int ntile = (c_len + kTile - 1) / kTile;
-        const int npc = min(ntile - c_kt, nspan - j);                    // tiles of this piece
-        // first tile of the piece: scores and softmax alone
-        scores(j);
-        __syncthreads();                                              // B1
-        sm_load(); sm_stage1(c_len - c_kt * kTile); sm_stage2(); sm_stage3(); sm_stage4(j & 1);
-        wait_own(1);
-        __syncthreads();                                              // B2
-        for (int k = 1; k < npc; ++k) {
-            scores(j + k);
-            pv_loads(j + k - 1);
-            __syncthreads();                                          // B1
-            pv(true, c_len - (c_kt + k) * kTile, (j + k) & 1);
-            wait_own(1);
-            __syncthreads();                                          // B2
+        // weighted sum of the tile at list position pos over this wavefront's columns:
+        // X^T[d, r] += sum_t H[t, d] P[r, t]
+        auto pv = [&](int pos) {
+            const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
+            const int buf = pos & 1;
+            // all operands are requested before the first MFMA
+            u4 P[NP];
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + (buf * NP + pl) * (32 * 16) + r32 * 16 + 8 * kg);
+            const float al = Ax[buf * 32 + r32];
+            constexpr int PF = MB < 3 ? MB : 3;                           // blocks whose transposing reads are in flight
+            s4 tb[MB][2];
+#pragma unroll
+            for (int mb = 0; mb < PF; ++mb) {
+                tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
+                tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
+            }
+            if (__any(al != 1.0f)) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) X[mb][i] *= al;
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (mb + PF < MB) {
+                    tb[mb + PF][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[(mb + PF) & 3] + ((mb + PF) >> 2) * 256));
+                    tb[mb + PF][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[(mb + PF) & 3] + ((mb + PF) >> 2) * 256));
+                }
+                const s4 lo = tb[mb][0], hi = tb[mb][1];
+                const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) X[mb] = Mma<BF16>::s32(hfrag, P[pl], X[mb]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // close a piece: X normalised by its own sum, straight from the accumulators (a lane holds four
+        // consecutive columns of one row: 8-byte stores, two lanes side by side, four instructions fill 64 bytes
+        // of each of 32 rows)
+        auto store_piece = [&](int b) {
+            const size_t slot = (size_t)(a.flat ? span + b : b);
+            const float inv = r32 < 16 * RG ? Linv[r32] : 0.f;
+            if (r32 < 16 * RG && row0 + r32 < a.R) {
+                f16_t *x_out = a.Xp + (slot * a.Rs + row0 + r32) * DM + DS * v + 4 * kg;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const h2 lo = __builtin_convertvector(f2{X[mb][4 * q4 + 0] * inv, X[mb][4 * q4 + 1] * inv}, h2);
+                        const h2 hi = __builtin_convertvector(f2{X[mb][4 * q4 + 2] * inv, X[mb][4 * q4 + 3] * inv}, h2);
+                        *(h4 *)(x_out + 32 * mb + 8 * q4) = h4{lo[0], lo[1], hi[0], hi[1]};
+                    }
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
+        };
+
+        fetch_next();
+        fetch_next();
+        int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
+        wait_own(0);
+        __syncthreads();                                              // S0
+        for (int j = 0;;) {
+            const int ntile = (c_len + kTile - 1) / kTile;
+            const int npc = min(ntile - c_kt, nspan - j);
+            for (int k = 0; k < npc; ++k) {
+                fetch_next();                                         // list position j + k + 2
+                __syncthreads();                                      // B1
+                if (k > 0) pv(j + k - 1);
+                wait_own(1);
+                __syncthreads();                                      // B2
+            }
+            j += npc;
+            pv(j - 1);                                                // the piece's last tile
+            __syncthreads();                                          // C1
+            store_piece(c_b);
+            if (j >= nspan) break;
+            ++c_b; c_kt = 0; c_len = elem_len(c_b);
+            __syncthreads();                                          // C2
         }
-        j += npc;
-        const bool more = j < nspan;
-        // the last tile's weighted sum; the next element's expanded queries are requested first (their registers are free)
-        if (more) load_elq(c_b + 1);
-        pv_loads(j - 1);
-        pv(false, 0, 0);
-        close_piece(c_b);
-        if (!more) break;
-        ++c_b; c_kt = 0; c_len = __builtin_amdgcn_readfirstlane(elem_len(c_b));
-        settle_elq();
-        __syncthreads();                                              // every wavefront is done with Linv and has tile j
+        // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-
-    // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 // ---------------------------------------------------------------------------------------------
