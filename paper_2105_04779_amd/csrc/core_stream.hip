@@ -101,7 +101,7 @@ k_core_stream(const StreamArgs a)
     static_assert(RG == 1 || RG == 2, "row groups per workgroup");
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
-    __shared__ __attribute__((aligned(16))) float Sx[4 * 64 * 4];             // partial scores [score wave][slot][4]
+    __shared__ __attribute__((aligned(16))) float Sx[2 * 4 * 64 * 4];         // partial scores [tile parity][score wave][slot][4]
     __shared__ __attribute__((aligned(16))) uint16_t Px[2 * NP * 32 * 16];    // probabilities [tile parity][plane][row][t]
     __shared__ float Ax[2 * 32];                                              // per-row rescale factor [tile parity][row]
     __shared__ float Linv[32];                                                // per-row 1/sum of the piece being closed
@@ -184,13 +184,14 @@ k_core_stream(const StreamArgs a)
     const int sr = l >> 2, sq = l & 3;                                    // softmax lane = 4 * row + position group
     const int sx_get = (4 * sr + (sq ^ (sr >> 2))) * 4;
 
-    // What crosses the barriers of tile j (list position):
-    //   B1(j): the partial scores of tile j are in LDS;
-    //   B2(j): P and the rescale factors of tile j are in LDS (buffer j&1; the weighted sum of tile j-1 read the
-    //          other buffer); every sum wavefront has left the weighted sum of tile j-1, so that tile's slot may
-    //          be refilled (tile j+3 goes there, requested after this barrier), and has waited for its own rows
-    //          of tile j+1.
-    // Both roles run the same sequence of barriers: B1, B2 per tile; C1, C2 where a piece is closed.
+    // The pipeline of a piece whose tiles sit at list positions j .. j+npc-1, one barrier per step i = 0 .. npc+1:
+    //   score wavefronts   scores of tile j+i (i < npc) into exchange buffer (j+i)&1, and, between those MFMAs,
+    //                      the softmax of tile j+i-1 (1 <= i <= npc) from the other buffer into P buffer (j+i-1)&1;
+    //   sum wavefronts     request tile j+i+2 (i < npc); weighted sum of tile j+i-2 (2 <= i) from the column
+    //                      fragments they hold in registers and P buffer (j+i-2)&1, each fragment replaced, as soon
+    //                      as it is consumed, by the one of tile j+i-1 (1 <= i <= npc) read from its slot.
+    // So a tile's slot is read in two consecutive steps (scores, then column fragments) and is free afterwards:
+    // two tiles are resident and two in flight.  Both roles run npc + 2 barriers per piece.
     if (w < 4) {
         // =========================== score wavefront ===========================
         const int rg = w / PARTS, part = w % PARTS;
@@ -215,55 +216,42 @@ k_core_stream(const StreamArgs a)
                 }
             }
         };
-        auto scores = [&](int pos) {
-            const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
-            // the fragment reads run PF chunks ahead of the MFMAs that use them: a read takes ~33 clocks to issue and
-            // ~100 to return, a pair of MFMAs 35, so the chain of MFMAs never waits and the reads issue in its shadow
-            constexpr int PF = CHK < 4 ? CHK : 4;
-            u4 hb[CHK];
-#pragma unroll
-            for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
-            f4 sc = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < CHK; ++c) {
-                __builtin_amdgcn_sched_barrier(0);
-                if (c + PF < CHK) hb[c + PF] = *(const EL_LDS(u4) *)(F + a_base[c + PF]);
-                sc = Mma<BF16>::s16(hb[c], elq[c][0], sc);
-                sc = Mma<BF16>::s16(hb[c], elq[c][1], sc);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            *(f4 *)(Sx + w * 256 + sx_put) = sc;
-        };
-        // softmax bookkeeping of this row group for one tile (owner only).  Lane = 4 * row + q holds positions
-        // 4q..4q+3 of its row, so a row's statistics stay inside a quad.  Branch-free: a row whose maximum does
-        // not grow gets the factor exp2(0) = 1.
+        // Softmax bookkeeping of this row group for one tile (owner only), in four stages that ride between the
+        // MFMAs of the next tile's scores.  Lane = 4 * row + q holds positions 4q..4q+3 of its row, so a row's
+        // statistics stay inside a quad.  Branch-free: a row whose maximum does not grow gets the factor exp2(0) = 1.
         float m_ref = -INFINITY, l_sum = 0.f;
-        auto softmax = [&](int lim_rows, int buf) {
-            if (!owner) return;
-            float sv[4], pr[4];
-            {
-                f4 st[PARTS];
+        f4 st[PARTS];
+        float sv[4], pr[4], alpha = 1.f;
+        auto sm_load = [&](int pos) {
 #pragma unroll
-                for (int p = 0; p < PARTS; ++p) st[p] = *(const f4 *)(Sx + (rg * PARTS + p) * 256 + sx_get);
-                const int lim = lim_rows - 4 * sq;                         // positions at or beyond the length do not exist
+            for (int p = 0; p < PARTS; ++p) st[p] = *(const f4 *)(Sx + (pos & 1) * 1024 + (rg * PARTS + p) * 256 + sx_get);
+        };
+        auto sm_stage1 = [&](int lim_rows) {                          // sum of the partials
+            const int lim = lim_rows - 4 * sq;                         // positions at or beyond the length do not exist
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float v = st[0][j];
+            for (int j = 0; j < 4; ++j) {
+                float v = st[0][j];
 #pragma unroll
-                    for (int p = 1; p < PARTS; ++p) v += st[p][j];
-                    sv[j] = j < lim ? v : -INFINITY;
-                }
+                for (int p = 1; p < PARTS; ++p) v += st[p][j];
+                sv[j] = j < lim ? v : -INFINITY;
             }
+        };
+        auto sm_stage2 = [&]() {                                      // row maximum, reference, rescale factor
             float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
             mx = fmaxf(mx, quad_xor1(mx));
             mx = fmaxf(mx, quad_xor2(mx));
             const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
             // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
-            const float alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
             m_ref = m_new;
+        };
+        auto sm_stage3 = [&]() {                                      // probabilities and running sum
             l_sum *= alpha;
 #pragma unroll
             for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
+        };
+        auto sm_stage4 = [&](int pos) {                               // publish P and the factors
+            const int buf = pos & 1;
             uint16_t *dst = Px + buf * (NP * 32 * 16) + (16 * rg + sr) * 16 + 4 * sq;
             if (BF16) {
                 // p = high + low, both bf16 by truncation: the pair carries 16 mantissa bits of p
@@ -281,25 +269,57 @@ k_core_stream(const StreamArgs a)
             }
             if (sq == 0) Ax[buf * 32 + 16 * rg + sr] = alpha;
         };
+        // chunk of the score product behind which each softmax stage is issued
+        constexpr int S1 = CHK / 5, S2 = 2 * CHK / 5, S3 = 3 * CHK / 5, S4 = 4 * CHK / 5;
+        // scores of the tile at list position pos over this wavefront's columns, left in LDS for the exchange;
+        // with sm (owner only), the softmax of the tile before it rides between the MFMAs.  The fragment reads
+        // run PF chunks ahead of the MFMAs that use them.
+        auto scores = [&](int pos, bool sm, int lim_rows) {
+            const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
+            constexpr int PF = CHK < 4 ? CHK : 4;
+            if (sm) sm_load(pos - 1);
+            u4 hb[CHK];
+#pragma unroll
+            for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
+            f4 sc = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < CHK; ++c) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (c + PF < CHK) hb[c + PF] = *(const EL_LDS(u4) *)(F + a_base[c + PF]);
+                sc = Mma<BF16>::s16(hb[c], elq[c][0], sc);
+                sc = Mma<BF16>::s16(hb[c], elq[c][1], sc);
+                if (sm) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (c == S1) sm_stage1(lim_rows);
+                    if (c == S2) sm_stage2();
+                    if (c == S3) sm_stage3();
+                    if (c == S4) sm_stage4(pos - 1);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            *(f4 *)(Sx + (pos & 1) * 1024 + w * 256 + sx_put) = sc;
+        };
 
         load_elq(b0);
         int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
-        __syncthreads();                                              // S0: the first two tiles have landed
+        __syncthreads();                                              // the first two tiles have landed
         for (int j = 0;;) {
             const int ntile = (c_len + kTile - 1) / kTile;
             const int npc = min(ntile - c_kt, nspan - j);                // tiles of this piece
-            for (int k = 0; k < npc; ++k) {
-                scores(j + k);
-                __syncthreads();                                      // B1
-                softmax(c_len - (c_kt + k) * kTile, (j + k) & 1);
-                __syncthreads();                                      // B2
+            const int rows0 = c_len - c_kt * kTile;                      // valid rows from the piece's first tile on
+            scores(j, false, 0);
+            __syncthreads();
+            for (int i = 1; i < npc; ++i) {
+                scores(j + i, owner, rows0 - (i - 1) * kTile);
+                __syncthreads();
             }
             j += npc;
             const bool more = j < nspan;
-            // the next element's expanded queries are requested while the sum wavefronts finish this one
+            // the next element's expanded queries are requested while this piece drains
             if (more) load_elq(c_b + 1);
-            // close the piece: this row group's statistics
             if (owner) {
+                // the softmax of the piece's last tile, then this row group's statistics
+                sm_load(j - 1); sm_stage1(rows0 - (npc - 1) * kTile); sm_stage2(); sm_stage3(); sm_stage4(j - 1);
                 l_sum += quad_xor1(l_sum);
                 l_sum += quad_xor2(l_sum);
                 const int row = row0 + 16 * rg + sr;
@@ -312,10 +332,10 @@ k_core_stream(const StreamArgs a)
                 }
             }
             m_ref = -INFINITY; l_sum = 0.f;
-            __syncthreads();                                          // C1: 1/sum of every row is in LDS
+            __syncthreads();                                          // step npc: P of the last tile and 1/sum are in LDS
+            __syncthreads();                                          // step npc+1: the sum wavefronts finish the piece
             if (!more) break;
             ++c_b; c_kt = 0; c_len = elem_len(c_b);
-            __syncthreads();                                          // C2: the sum wavefronts are done with the piece
         }
     } else {
         // =========================== sum wavefront ===========================
@@ -351,9 +371,8 @@ k_core_stream(const StreamArgs a)
                 const int row = 4 * v + i;
                 const bool ok = row < rows;                                // wave-uniform
                 const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB : (const char *)a.H - i * ROWB;
-                const unsigned voff = (unsigned)(((l ^ ((i << 2) | v)) << 4) + i * ROWB);   // tile_swizzle(4v + i)
                 const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
-                dma(dst, voff, sbase);
+                dma(dst, voff4[i], sbase);
                 if (live && !ok) {
 #pragma unroll
                     for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
@@ -390,41 +409,40 @@ k_core_stream(const StreamArgs a)
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
+        s4 tb[MB][2];                                    // column fragments of the tile whose weighted sum comes next
 
-        // weighted sum of the tile at list position pos over this wavefront's columns:
-        // X^T[d, r] += sum_t H[t, d] P[r, t]
-        auto pv = [&](int pos) {
-            const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
-            const int buf = pos & 1;
-            // all operands are requested before the first MFMA
+        // One step of the sum role: X^T[d, r] += sum_t H[t, d] P[r, t] for the tile whose fragments are held
+        // (do_pv; P and the factors from buffer pv_pos&1), each fragment replaced, once consumed, by the one of
+        // the tile at list position ld_pos (do_ld).
+        auto step = [&](bool do_pv, int pv_pos, bool do_ld, int ld_pos) {
+            const EL_LDS(char) *F = Tl + (ld_pos & 3) * SLOT;
             u4 P[NP];
+            float al = 1.f;
+            if (do_pv) {
+                const int buf = pv_pos & 1;
 #pragma unroll
-            for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + (buf * NP + pl) * (32 * 16) + r32 * 16 + 8 * kg);
-            const float al = Ax[buf * 32 + r32];
-            constexpr int PF = MB < 3 ? MB : 3;                           // blocks whose transposing reads are in flight
-            s4 tb[MB][2];
+                for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + (buf * NP + pl) * (32 * 16) + r32 * 16 + 8 * kg);
+                al = Ax[buf * 32 + r32];
+                if (__any(al != 1.0f)) {
 #pragma unroll
-            for (int mb = 0; mb < PF; ++mb) {
-                tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
-                tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
-            }
-            if (__any(al != 1.0f)) {
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) X[mb][i] *= al;
+                        for (int i = 0; i < 16; ++i) X[mb][i] *= al;
+                }
             }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (mb + PF < MB) {
-                    tb[mb + PF][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[(mb + PF) & 3] + ((mb + PF) >> 2) * 256));
-                    tb[mb + PF][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[(mb + PF) & 3] + ((mb + PF) >> 2) * 256));
-                }
-                const s4 lo = tb[mb][0], hi = tb[mb][1];
-                const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+                if (do_pv) {
+                    const s4 lo = tb[mb][0], hi = tb[mb][1];
+                    const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
 #pragma unroll
-                for (int pl = 0; pl < NP; ++pl) X[mb] = Mma<BF16>::s32(hfrag, P[pl], X[mb]);
+                    for (int pl = 0; pl < NP; ++pl) X[mb] = Mma<BF16>::s32(hfrag, P[pl], X[mb]);
+                }
+                if (do_ld) {
+                    tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
+                    tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         };
@@ -455,26 +473,27 @@ k_core_stream(const StreamArgs a)
         fetch_next();
         int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
         wait_own(0);
-        __syncthreads();                                              // S0
+        __syncthreads();                                              // the first two tiles have landed
         for (int j = 0;;) {
             const int ntile = (c_len + kTile - 1) / kTile;
             const int npc = min(ntile - c_kt, nspan - j);
-            for (int k = 0; k < npc; ++k) {
-                fetch_next();                                         // list position j + k + 2
-                __syncthreads();                                      // B1
-                if (k > 0) pv(j + k - 1);
+            for (int i = 0; i < npc; ++i) {
+                fetch_next();                                         // list position j + i + 2
+                if (i == 1) step(false, 0, true, j);
+                if (i >= 2) step(true, j + i - 2, true, j + i - 1);
                 wait_own(1);
-                __syncthreads();                                      // B2
+                __syncthreads();
             }
             j += npc;
-            pv(j - 1);                                                // the piece's last tile
-            __syncthreads();                                          // C1
+            if (npc >= 2) step(true, j - 2, true, j - 1);             // step npc
+            else step(false, 0, true, j - 1);
+            __syncthreads();
+            step(true, j - 1, false, 0);                              // step npc + 1
             store_piece(c_b);
+            __syncthreads();
             if (j >= nspan) break;
             ++c_b; c_kt = 0; c_len = elem_len(c_b);
-            __syncthreads();                                          // C2
         }
-        // the last fetches went to the dump area; none may be in flight when the workgroup gives up its LDS
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 }
