@@ -216,88 +216,98 @@ k_core_stream(const StreamArgs a)
                 }
             }
         };
-        // Softmax bookkeeping of this row group for one tile (owner only), in four stages that ride between the
-        // MFMAs of the next tile's scores.  Lane = 4 * row + q holds positions 4q..4q+3 of its row, so a row's
-        // statistics stay inside a quad.  Branch-free: a row whose maximum does not grow gets the factor exp2(0) = 1.
+        // Softmax bookkeeping of this row group for one tile (owner only), cut into twelve small stages that ride
+        // between the MFMAs of the next tile's scores (a stage is a few vector instructions: they issue while the
+        // matrix unit works, a longer run of them would hold the chain of MFMAs up).  Lane = 4 * row + q holds
+        // positions 4q..4q+3 of its row, so a row's statistics stay inside a quad.  Branch-free: a row whose
+        // maximum does not grow gets the factor exp2(0) = 1.
         float m_ref = -INFINITY, l_sum = 0.f;
         f4 st[PARTS];
-        float sv[4], pr[4], alpha = 1.f;
+        float sv[4], pr[4], alpha = 1.f, mx = 0.f;
+        unsigned ph[4], plo[4];
+        int sm_lim = 0;
         auto sm_load = [&](int pos) {
 #pragma unroll
             for (int p = 0; p < PARTS; ++p) st[p] = *(const f4 *)(Sx + (pos & 1) * 1024 + (rg * PARTS + p) * 256 + sx_get);
         };
-        auto sm_stage1 = [&](int lim_rows) {                          // sum of the partials
-            const int lim = lim_rows - 4 * sq;                         // positions at or beyond the length do not exist
+        auto sm_sum = [&](int j) {                                    // sum of the partials of position 4q + j
+            float v = st[0][j];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float v = st[0][j];
-#pragma unroll
-                for (int p = 1; p < PARTS; ++p) v += st[p][j];
-                sv[j] = j < lim ? v : -INFINITY;
-            }
+            for (int p = 1; p < PARTS; ++p) v += st[p][j];
+            sv[j] = j < sm_lim ? v : -INFINITY;                         // positions at or beyond the length do not exist
         };
-        auto sm_stage2 = [&]() {                                      // row maximum, reference, rescale factor
-            float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-            mx = fmaxf(mx, quad_xor1(mx));
-            mx = fmaxf(mx, quad_xor2(mx));
-            const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
-            // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
-            alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
-            m_ref = m_new;
+        auto sm_prob = [&](int j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; };
+        auto sm_split = [&](int j) {                                  // p = high + low, both bf16 by truncation
+            ph[j] = __float_as_uint(pr[j]) & 0xffff0000u;
+            plo[j] = __float_as_uint(pr[j] - __uint_as_float(ph[j]));
         };
-        auto sm_stage3 = [&]() {                                      // probabilities and running sum
-            l_sum *= alpha;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
-        };
-        auto sm_stage4 = [&](int pos) {                               // publish P and the factors
+        auto sm_stage = [&](int k, int pos) {
             const int buf = pos & 1;
             uint16_t *dst = Px + buf * (NP * 32 * 16) + (16 * rg + sr) * 16 + 4 * sq;
-            if (BF16) {
-                // p = high + low, both bf16 by truncation: the pair carries 16 mantissa bits of p
-                unsigned hi[4], lo[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    hi[j] = __float_as_uint(pr[j]) & 0xffff0000u;
-                    lo[j] = __float_as_uint(pr[j] - __uint_as_float(hi[j]));
-                }
-                *(u2 *)dst = u2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
-                *(u2 *)(dst + 32 * 16) = u2{(lo[0] >> 16) | (lo[1] & 0xffff0000u), (lo[2] >> 16) | (lo[3] & 0xffff0000u)};
-            } else {
-                const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
-                *(h4 *)dst = h4{p01[0], p01[1], p23[0], p23[1]};
+            switch (k) {
+            case 0: sm_sum(0); sm_sum(1); break;
+            case 1: sm_sum(2); sm_sum(3); break;
+            case 2: mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])); mx = fmaxf(mx, quad_xor1(mx)); break;
+            case 3: mx = fmaxf(mx, quad_xor2(mx)); break;
+            case 4: {
+                const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
+                // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
+                alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
+                m_ref = m_new;
+                l_sum *= alpha;
+                break;
             }
-            if (sq == 0) Ax[buf * 32 + 16 * rg + sr] = alpha;
+            case 5: sm_prob(0); sm_prob(1); break;
+            case 6: sm_prob(2); sm_prob(3); break;
+            case 7: if (BF16) { sm_split(0); sm_split(1); } break;
+            case 8: if (BF16) { sm_split(2); sm_split(3); } break;
+            case 9:
+                if (BF16) *(u2 *)dst = u2{(ph[0] >> 16) | ph[1], (ph[2] >> 16) | ph[3]};
+                else {
+                    const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
+                    *(h4 *)dst = h4{p01[0], p01[1], p23[0], p23[1]};
+                }
+                break;
+            case 10:
+                if (BF16) *(u2 *)(dst + 32 * 16) = u2{(plo[0] >> 16) | (plo[1] & 0xffff0000u), (plo[2] >> 16) | (plo[3] & 0xffff0000u)};
+                break;
+            default: Ax[buf * 32 + 16 * rg + sr] = alpha; break;      // the four lanes of a quad write the same value
+            }
         };
-        // chunk of the score product behind which each softmax stage is issued
-        constexpr int S1 = CHK / 5, S2 = 2 * CHK / 5, S3 = 3 * CHK / 5, S4 = 4 * CHK / 5;
+        constexpr int NST = 12;
         // scores of the tile at list position pos over this wavefront's columns, left in LDS for the exchange;
-        // with sm (owner only), the softmax of the tile before it rides between the MFMAs.  The fragment reads
+        // with SM (owner only), the softmax of the tile before it rides between the MFMAs.  The fragment reads
         // run PF chunks ahead of the MFMAs that use them.
-        auto scores = [&](int pos, bool sm, int lim_rows) {
+        auto scores = [&](int pos, auto sm_tag, int lim_rows) {
+            constexpr bool SM = decltype(sm_tag)::value;
             const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
             constexpr int PF = CHK < 4 ? CHK : 4;
-            if (sm) sm_load(pos - 1);
+            if (SM) { sm_load(pos - 1); sm_lim = lim_rows - 4 * sq; }
             u4 hb[CHK];
 #pragma unroll
             for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
-            f4 sc = f4{0.f, 0.f, 0.f, 0.f};
+            // two chains of MFMAs (high plane, low plane), so that no MFMA waits for the one issued just before it
+            f4 sc = f4{0.f, 0.f, 0.f, 0.f}, sc2 = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int c = 0; c < CHK; ++c) {
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + PF < CHK) hb[c + PF] = *(const EL_LDS(u4) *)(F + a_base[c + PF]);
                 sc = Mma<BF16>::s16(hb[c], elq[c][0], sc);
-                sc = Mma<BF16>::s16(hb[c], elq[c][1], sc);
-                if (sm) {
+                if (SM) {
+#pragma unroll
+                    for (int k = 0; k < NST; ++k)
+                        if ((2 * k * CHK) / NST == 2 * c) sm_stage(k, pos - 1);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (c == S1) sm_stage1(lim_rows);
-                    if (c == S2) sm_stage2();
-                    if (c == S3) sm_stage3();
-                    if (c == S4) sm_stage4(pos - 1);
+                }
+                sc2 = Mma<BF16>::s16(hb[c], elq[c][1], sc2);
+                if (SM) {
+#pragma unroll
+                    for (int k = 0; k < NST; ++k)
+                        if ((2 * k * CHK) / NST == 2 * c + 1) sm_stage(k, pos - 1);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            *(f4 *)(Sx + (pos & 1) * 1024 + w * 256 + sx_put) = sc;
+            *(f4 *)(Sx + (pos & 1) * 1024 + w * 256 + sx_put) = f4{sc[0] + sc2[0], sc[1] + sc2[1], sc[2] + sc2[2], sc[3] + sc2[3]};
         };
 
         load_elq(b0);
@@ -307,10 +317,11 @@ k_core_stream(const StreamArgs a)
             const int ntile = (c_len + kTile - 1) / kTile;
             const int npc = min(ntile - c_kt, nspan - j);                // tiles of this piece
             const int rows0 = c_len - c_kt * kTile;                      // valid rows from the piece's first tile on
-            scores(j, false, 0);
+            scores(j, std::false_type{}, 0);
             __syncthreads();
             for (int i = 1; i < npc; ++i) {
-                scores(j + i, owner, rows0 - (i - 1) * kTile);
+                if (owner) scores(j + i, std::true_type{}, rows0 - (i - 1) * kTile);
+                else scores(j + i, std::false_type{}, 0);
                 __syncthreads();
             }
             j += npc;
@@ -319,7 +330,9 @@ k_core_stream(const StreamArgs a)
             if (more) load_elq(c_b + 1);
             if (owner) {
                 // the softmax of the piece's last tile, then this row group's statistics
-                sm_load(j - 1); sm_stage1(rows0 - (npc - 1) * kTile); sm_stage2(); sm_stage3(); sm_stage4(j - 1);
+                sm_load(j - 1); sm_lim = rows0 - (npc - 1) * kTile - 4 * sq;
+#pragma unroll
+                for (int k = 0; k < NST; ++k) sm_stage(k, j - 1);
                 l_sum += quad_xor1(l_sum);
                 l_sum += quad_xor2(l_sum);
                 const int row = row0 + 16 * rg + sr;
@@ -355,29 +368,24 @@ k_core_stream(const StreamArgs a)
         unsigned voff4[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) voff4[i] = (unsigned)(((l ^ ((i << 2) | v)) << 4) + i * ROWB);    // tile_swizzle(4v + i)
-        auto fetch_next = [&]() {
+        // the request of one tile, row by row, so that the weighted sum can spread the four requests over its MFMAs
+        // (a request holds its wavefront up while the address unit is busy with the other wavefronts' requests)
+        auto fetch_row = [&](int i) {
             const int slot = f_pos & 3;
             const bool live = f_pos < nspan;
             const int rows = live ? f_len - f_kt * kTile : 0;          // valid rows of this tile (may exceed 16)
-            if (rows >= kTile) {
-                // the common case, a whole tile: one source base, four destinations, no per-row choices
-                const char *sbase = f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB;
-                const unsigned dst0 = t_lds + slot * SLOT + 4 * v * ROWB;
+            const int row = 4 * v + i;
+            const bool ok = row < rows;                                    // wave-uniform
+            const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB : (const char *)a.H - i * ROWB;
+            const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
+            dma(dst, voff4[i], sbase);
+            if (live && !ok) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) dma(dst0 + i * ROWB, voff4[i], sbase);
-            } else
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = 4 * v + i;
-                const bool ok = row < rows;                                // wave-uniform
-                const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB : (const char *)a.H - i * ROWB;
-                const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
-                dma(dst, voff4[i], sbase);
-                if (live && !ok) {
-#pragma unroll
-                    for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
-                }
+                for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
             }
+        };
+        auto fetch_advance = [&]() {
+            const bool live = f_pos < nspan;
             ++f_pos;
             if (live) {
                 if (++f_kt * kTile >= f_len) {
@@ -386,6 +394,11 @@ k_core_stream(const StreamArgs a)
                     f_H = (const char *)a.H + (size_t)min(f_b, a.B - 1) * a.h_stride * 2;
                 }
             }
+        };
+        auto fetch_next = [&]() {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fetch_row(i);
+            fetch_advance();
         };
         // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
         auto wait_own = [&](int later_tiles) {
@@ -414,7 +427,7 @@ k_core_stream(const StreamArgs a)
         // One step of the sum role: X^T[d, r] += sum_t H[t, d] P[r, t] for the tile whose fragments are held
         // (do_pv; P and the factors from buffer pv_pos&1), each fragment replaced, once consumed, by the one of
         // the tile at list position ld_pos (do_ld).
-        auto step = [&](bool do_pv, int pv_pos, bool do_ld, int ld_pos) {
+        auto step = [&](bool do_pv, int pv_pos, bool do_ld, int ld_pos, bool do_fetch) {
             const EL_LDS(char) *F = Tl + (ld_pos & 3) * SLOT;
             u4 P[NP];
             float al = 1.f;
@@ -430,20 +443,26 @@ k_core_stream(const StreamArgs a)
                         for (int i = 0; i < 16; ++i) X[mb][i] *= al;
                 }
             }
+            u4 hprev = u4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 __builtin_amdgcn_sched_barrier(0);
                 if (do_pv) {
+                    // plane 0 of this block, then plane 1 of the block before it: no MFMA waits for its predecessor
                     const s4 lo = tb[mb][0], hi = tb[mb][1];
                     const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-#pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) X[mb] = Mma<BF16>::s32(hfrag, P[pl], X[mb]);
+                    X[mb] = Mma<BF16>::s32(hfrag, P[0], X[mb]);
+                    if (NP == 2 && mb > 0) X[mb - 1] = Mma<BF16>::s32(hprev, P[1], X[mb - 1]);
+                    hprev = hfrag;
                 }
                 if (do_ld) {
                     tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
                     tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
                 }
+                if (do_fetch && mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
             }
+            if (do_pv && NP == 2) X[MB - 1] = Mma<BF16>::s32(hprev, P[1], X[MB - 1]);
+            if (do_fetch) fetch_advance();
             __builtin_amdgcn_sched_barrier(0);
         };
         // close a piece: X normalised by its own sum, straight from the accumulators (a lane holds four
@@ -478,17 +497,18 @@ k_core_stream(const StreamArgs a)
             const int ntile = (c_len + kTile - 1) / kTile;
             const int npc = min(ntile - c_kt, nspan - j);
             for (int i = 0; i < npc; ++i) {
-                fetch_next();                                         // list position j + i + 2
-                if (i == 1) step(false, 0, true, j);
-                if (i >= 2) step(true, j + i - 2, true, j + i - 1);
+                // list position j + i + 2 is requested in every step
+                if (i == 0) fetch_next();
+                if (i == 1) step(false, 0, true, j, true);
+                if (i >= 2) step(true, j + i - 2, true, j + i - 1, true);
                 wait_own(1);
                 __syncthreads();
             }
             j += npc;
-            if (npc >= 2) step(true, j - 2, true, j - 1);             // step npc
-            else step(false, 0, true, j - 1);
+            if (npc >= 2) step(true, j - 2, true, j - 1, false);      // step npc
+            else step(false, 0, true, j - 1, false);
             __syncthreads();
-            step(true, j - 1, false, 0);                              // step npc + 1
+            step(true, j - 1, false, 0, false);                       // step npc + 1
             store_piece(c_b);
             __syncthreads();
             if (j >= nspan) break;
