@@ -201,30 +201,32 @@ el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq
                                int32_t B, int32_t beam, void *stream);
 
 /*
- * Tuning knob, never semantics: number of contiguous key-range splits the
- * attention core uses per batch element (each split is one workgroup; partial
- * results are merged with the log-sum-exp rule).  0 restores the automatic
- * choice.  Must not exceed el_attn_max_splits().
+ * Tuning knob, never semantics: about how many pieces per batch element the attention core
+ * cuts the keys into (the MFMA core cuts the list of all valid 16-row tiles of a batch into
+ * B x splits equal spans, one workgroup each per block of rows; the generic core cuts every
+ * element into `splits` key ranges; partial results are merged with the log-sum-exp rule).
+ * 0 restores the automatic choice.  Must not exceed el_attn_max_splits().
  */
 el_status el_attn_set_splits(el_attn_ctx *ctx, int32_t splits);
 int32_t el_attn_max_splits(void);
 
 /*
  * Second tuning knob, never semantics: how many 16-row groups of expanded queries one
- * workgroup of the MFMA attention core owns (1, 2 or 4; 0 restores the automatic choice).
- * With fewer rows per workgroup, several workgroups stream the same H range (served by
- * the shared L2 after the first touch) and fewer key-range splits are needed.
+ * workgroup of the MFMA attention core owns (1 or 2; 0 restores the automatic choice, which
+ * is 2 wherever the shape has more than 16 rows).  The row blocks of one span stream the
+ * same H tiles (served by the shared L2 after the first touch).
  */
 el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups);
 
 /*
  * What the automatic choice would be for a shape on a device with `compute_units` compute units (host
- * arithmetic only, no device needed): rows per workgroup in groups of 16 (*row_groups) and key ranges
- * per batch element (*splits) of the MFMA attention core.  Errors: INVALID_ARG (null outputs, sizes < 1),
- * UNSUPPORTED (d_model other than 512 or 1024: no MFMA core).
+ * arithmetic only, no device needed): rows per workgroup in groups of 16 (*row_groups) and the number of
+ * equal spans the list of valid tiles is cut into (*spans; workgroups = spans x row blocks) by the MFMA
+ * attention core.  Errors: INVALID_ARG (null outputs, sizes < 1), UNSUPPORTED (d_model other than 512 or
+ * 1024: no MFMA core).
  */
 el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,
-                               int32_t compute_units, int32_t *row_groups, int32_t *splits);
+                               int32_t compute_units, int32_t *row_groups, int32_t *spans);
 
 /* 1 if decode_step on this context runs the MFMA kernels, 0 if the generic fp32 ones. */
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);

@@ -1,7 +1,7 @@
 // Planning and launch of the MFMA attention core (steps a3-a5 of the EL-attention decode step; the
 // kernel itself is in core_stream.hip), plus the two small fp32-FMA kernels that stand in for the MFMA
 // projections around it when the head size is not 64: the query expansion as a high + low pair of
-// 16-bit planes and the log-sum-exp merge of the pieces.
+// 16-bit planes (in the fragment order the core loads) and the log-sum-exp merge of the pieces.
 #include <cmath>
 #include <cstdlib>
 #include "el_internal.h"
@@ -11,8 +11,8 @@ namespace el {
 // a2 for the MFMA core: EL-Q pre-multiplied by log2(e) (Qp already carries 1/sqrt(d_k)), as a high and a
 // low plane in the storage type.
 template <typename T, bool BF16>
-__global__ void k_elq_planes(const float *__restrict__ Qp, const T *__restrict__ Wk, uint16_t *__restrict__ hi,
-                             uint16_t *__restrict__ lo, int beam, int d_m, int d_k, int hd, int R, int Rs)
+__global__ void k_elq_planes(const float *__restrict__ Qp, const T *__restrict__ Wk, uint16_t *__restrict__ planes,
+                             int beam, int d_m, int d_k, int hd, int R, int Rs)
 {
     const int d = blockIdx.x * 256 + threadIdx.x;
     const int r = blockIdx.y, b = blockIdx.z;
@@ -23,8 +23,7 @@ __global__ void k_elq_planes(const float *__restrict__ Qp, const T *__restrict__
     float acc = 0.f;
     for (int c = 0; c < d_k; ++c) acc = fmaf(qp[c], to_f32(wk[c]), acc);
     acc *= 1.4426950408889634f;
-    const size_t o = ((size_t)b * Rs + r) * d_m + d;
-    split16<BF16>(acc, hi[o], lo[o]);
+    split16<BF16>(acc, planes[elq_frag_index(b, r, d, 0, Rs, d_m)], planes[elq_frag_index(b, r, d, 1, Rs, d_m)]);
 }
 
 // Log-sum-exp merge of normalised fp16 pieces (reference maxima in log2 units):
@@ -113,13 +112,13 @@ hipError_t launch_elq_f16(const el_attn_ctx *ctx, const Problem &p, const Worksp
                           hipStream_t s)
 {
     const dim3 grid((p.d_m + 255) / 256, p.R, p.B), block(256);
-    uint16_t *hi = (uint16_t *)ws.ELQ, *lo = hi + (size_t)p.B * pl.Rs * p.d_m;
+    uint16_t *planes = (uint16_t *)ws.ELQ;
     if (p.dtype == EL_F16)
         hipLaunchKernelGGL((k_elq_planes<f16_t, false>), grid, block, 0, s, (const float *)ws.Qp, (const f16_t *)ctx->w.Wk,
-                           hi, lo, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
+                           planes, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
     else
         hipLaunchKernelGGL((k_elq_planes<bf16_t, true>), grid, block, 0, s, (const float *)ws.Qp, (const bf16_t *)ctx->w.Wk,
-                           hi, lo, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
+                           planes, p.beam, p.d_m, p.d_k, p.hd, p.R, pl.Rs);
     return hipGetLastError();
 }
 
@@ -128,7 +127,7 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
 {
     StreamArgs a;
     a.H = p.H; a.h_stride = p.H_batch_stride; a.lengths = p.lengths;
-    a.elq_hi = (const uint16_t *)ws.ELQ; a.elq_lo = a.elq_hi + (size_t)p.B * pl.Rs * p.d_m;
+    a.elq = (const uint16_t *)ws.ELQ;
     a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML; a.E = pl.flat ? ws.E : nullptr;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.nblocks = pl.nblocks;
     a.flat = pl.flat; a.G = pl.G; a.lfloor = pl.lfloor;

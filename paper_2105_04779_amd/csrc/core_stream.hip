@@ -6,29 +6,33 @@
 // expanded-query rows, so every compute unit streams the same number of bytes whatever the lengths
 // are.  Where a span crosses from one batch element to the next the workgroup closes a PIECE: it
 // writes that element's partial result (normalised by its own sum, with the softmax statistics) to
-// slot `span + element` and starts the next element with fresh statistics; a6 merges an element's
-// pieces by the log-sum-exp rule.  An element that lies inside one span has one piece and needs no
-// merge.
+// slot `span + element` and goes on with the next element without draining its pipeline; a6 merges
+// an element's pieces by the log-sum-exp rule.  An element that lies inside one span has one piece
+// and needs no merge.
 //
-// A workgroup is eight wavefronts, two per SIMD, with two roles, so that on every SIMD the LDS
-// traffic and dependent chains of one role hide behind the MFMAs of the other:
+// On this hardware an LDS instruction holds its wavefront for about as long as an MFMA does (~32
+// clocks), and a wavefront issues in order, so the work of a tile is spread over eight wavefronts,
+// two per SIMD, with two roles of about equal issue time:
 //
-//   score wavefronts (0..3)   own one 16-row group of expanded queries and 1/2 or 1/4 of the model
-//       dimension.  S^T[t, r] partial over those columns: 16x16x32 MFMA in the STORAGE type, A = H rows
-//       (ds_read_b128), B = the wavefront's slice of EL-Q held in registers as a high + low pair of
-//       16-bit values (two MFMAs), so a score keeps ~16 mantissa bits however peaked the softmax
-//       is, and bf16 H enters the MFMA as it is.  The partials of a row group meet in LDS; its first
-//       wavefront sums them and does the softmax bookkeeping in fp32 (running reference maximum,
-//       advanced only when it would grow by more than 2^10), then publishes P (fp16, or a high + low
-//       bf16 pair) and the rescale factors.
+//   score wavefronts (0..3)   own a quarter of the model dimension for all rows of the workgroup.
+//       S^T[t, r] partial over those columns: 16x16x32 MFMA in the STORAGE type, A = H rows (one
+//       ds_read_b128 feeds the MFMAs of both row groups and both planes), B = the wavefront's slice of
+//       EL-Q held in registers as a high + low pair of 16-bit values, so a score keeps ~16 mantissa
+//       bits however peaked the softmax is, and bf16 H enters the MFMA as it is.  The four partials
+//       meet in LDS; one step later each score wavefront sums them for a quarter of the rows and does
+//       the softmax bookkeeping in fp32 (running reference maximum, advanced only when it would grow
+//       by more than 2^10), then publishes P (fp16, or a high + low bf16 pair), the rescale factors
+//       and, where a piece ends, 1/sum.
 //   sum wavefronts (4..7)     own a quarter of the model dimension: X^T[d, r] += H^T[d, t] P^T[t, r],
 //       32x32x16 MFMA, A = H columns through the transposing LDS read (ds_read_b64_tr_b16), B = P from
 //       LDS, fp32 accumulators.  They also request the tiles: each 1 KB piece of a tile row goes
-//       straight from HBM into one of four LDS tile slots (global_load_lds; two tiles are outstanding
-//       while two are in use), across piece boundaries as well.  Lane i of a 1 KB piece fetches chunk
-//       i ^ swizzle(row), which keeps both operand read patterns spread over all banks.
+//       straight from HBM into one of four LDS tile slots (global_load_lds), across piece boundaries
+//       as well.  Lane i of a 1 KB piece fetches chunk i ^ swizzle(row), which keeps both operand read
+//       patterns spread over all banks.
 //
-// Scores and softmax of a tile run one tile ahead of its weighted sum; two barriers per tile.
+// One barrier per tile.  In step i the scores of tile i, the softmax of tile i-1 and the weighted sum
+// of tile i-2 run side by side; the sum wavefronts take tile i's column fragments into registers in
+// the same step, so a slot is read in one step only: one tile is resident, three are in flight.
 // Scores arrive pre-multiplied by log2(e)/sqrt(d_k), so the softmax is an exp2 of a difference.
 #include <type_traits>
 #include <hip/hip_ext.h>
@@ -62,6 +66,8 @@ __device__ __forceinline__ int tile_swizzle(int row) { return ((row & 3) << 2) |
 
 // butterfly over the four lanes of a quad on the VALU (DPP quad_perm), no LDS round trip
 __device__ __forceinline__ float quad_xor1(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true)); }
+__device__ __forceinline__ float dpp_half_mirror(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true)); }   // lane i <-> 7 - i of each 8
+__device__ __forceinline__ float dpp_row_mirror(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true)); }    // lane i <-> 15 - i of each 16
 __device__ __forceinline__ float quad_xor2(float v) { return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true)); }
 
 template <bool BF16> struct Mma;
@@ -83,7 +89,7 @@ __device__ __forceinline__ int wave_sum(int v)
 
 } // namespace
 
-template <int DM, bool BF16, int RG>
+template <int DM, bool BF16, int RG, bool NT>
 __global__ void __launch_bounds__(512)
 k_core_stream(const StreamArgs a)
 {
@@ -92,19 +98,24 @@ k_core_stream(const StreamArgs a)
     constexpr int NSLOT = 4;
     constexpr int PIECES = ROWB / 1024;             // 1 KB LDS-DMA pieces per row
     constexpr int NI = 4 * PIECES;                  // fetch instructions per sum wavefront per tile (four rows)
-    constexpr int PARTS = 4 / RG;                   // score wavefronts per row group (column parts)
-    constexpr int CHK = DM / 32 / PARTS;            // 32-column chunks of one score wavefront
+    constexpr int CHK = DM / 128;                   // 32-column chunks of one score wavefront (a quarter of the columns)
     constexpr int DS = DM / 4;                      // columns per sum wavefront
     constexpr int MB = DS / 32;                     // 32-column blocks of the output per sum wavefront
     constexpr int NP = BF16 ? 2 : 1;                // 16-bit planes of P
+    constexpr int ROWS = 16 * RG;                   // expanded-query rows of this workgroup
+    constexpr int SXP = ROWS * 16;                  // floats of one part of one exchange buffer [row][position]
+    constexpr int SXB = 4 * SXP;                    // one exchange buffer (four column parts)
+    constexpr int TPL = RG;                         // positions per softmax lane
+    constexpr int LPR = 16 / TPL;                   // softmax lanes per row
+    constexpr int RPW = 64 / LPR;                   // rows whose softmax one score wavefront does (= ROWS / 4)
     static_assert(DM == 512 || DM == 1024, "d_m is 512 or 1024");
     static_assert(RG == 1 || RG == 2, "row groups per workgroup");
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
-    __shared__ __attribute__((aligned(16))) float Sx[2 * 4 * 64 * 4];         // partial scores [tile parity][score wave][slot][4]
-    __shared__ __attribute__((aligned(16))) uint16_t Px[2 * NP * 32 * 16];    // probabilities [tile parity][plane][row][t]
+    __shared__ __attribute__((aligned(16))) float Sx[2 * SXB];                // partial scores [tile parity][part][row][position]
+    __shared__ __attribute__((aligned(16))) uint16_t Px[2 * NP * 32 * 16];    // probabilities [tile parity][plane][row][position]
     __shared__ float Ax[2 * 32];                                              // per-row rescale factor [tile parity][row]
-    __shared__ float Linv[32];                                                // per-row 1/sum of the piece being closed
+    __shared__ float Linv[2 * 32];                                            // per-row 1/sum of a piece [parity of its last tile][row]
     __shared__ __attribute__((aligned(1024))) char Dz[ROWB];                  // where fetches of rows that do not exist land
     __shared__ int Lt[kScanMax];                                              // clamped lengths of all batch elements (flattened cut)
 
@@ -120,12 +131,12 @@ k_core_stream(const StreamArgs a)
     const int place = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (place >= nwg) return;
     const int span = place / a.nblocks, rb = place % a.nblocks;
-    const int row0 = rb * (16 * RG);                 // first expanded-query row of this workgroup
+    const int row0 = rb * ROWS;                      // first expanded-query row of this workgroup
 
     auto clamp_len = [&](int v) { return min(max(v, 1), a.n); };
 
     // ---- where this span starts: element b0, tile kt0 of it, nspan tiles in all ----
-    int b0, kt0, nspan;
+    int b0, kt0, nspan, len0;
     if (a.flat) {
         for (int i = tid; i < a.B; i += 512) Lt[i] = clamp_len(a.lengths ? a.lengths[i] : a.n);
         __syncthreads();
@@ -160,251 +171,273 @@ k_core_stream(const StreamArgs a)
         b0 = __builtin_amdgcn_readfirstlane(b0);
         kt0 = __builtin_amdgcn_readfirstlane(kt0);
         if (nspan <= 0 || b0 < 0) return;            // the list is shorter than G spans of the floor length
+        len0 = __builtin_amdgcn_readfirstlane(Lt[b0]);
     } else {
         b0 = span; kt0 = 0;
-        nspan = (clamp_len(a.lengths ? a.lengths[b0] : a.n) + kTile - 1) / kTile;
+        len0 = __builtin_amdgcn_readfirstlane(clamp_len(a.lengths ? a.lengths[b0] : a.n));
+        nspan = (len0 + kTile - 1) / kTile;
     }
-    auto elem_len = [&](int b) -> int {
-        int v;
-        if (a.flat) v = b < a.B ? Lt[b] : kTile;
-        else v = clamp_len(a.lengths ? a.lengths[min(b, a.B - 1)] : a.n);
-        return __builtin_amdgcn_readfirstlane(v);
+    // length of an element the span moves on to (only the flattened cut crosses elements)
+    auto next_len = [&](int b) -> int { return __builtin_amdgcn_readfirstlane(a.flat && b < a.B ? Lt[b] : kTile); };
+    // a cursor over the span's tiles: element, tile of it, the element's length
+    struct Cursor {
+        int b, kt, len;
+        __device__ __forceinline__ int rows() const { return len - kt * kTile; }          // valid rows from this tile on
+        __device__ __forceinline__ bool elem_last() const { return rows() <= kTile; }
+    };
+    auto advance = [&](Cursor &c) {
+        if (c.elem_last()) { ++c.b; c.kt = 0; c.len = next_len(c.b); } else ++c.kt;
     };
 
     const EL_LDS(char) *Tl = (const EL_LDS(char) *)T;
     const unsigned t_lds = (unsigned)(uintptr_t)Tl;
     const unsigned dz_lds = (unsigned)(uintptr_t)(const EL_LDS(char) *)Dz;
 
+    // before the first barrier: no probabilities yet (the sum wavefronts multiply by them from step 0 on)
     if (tid < 2 * 32) Ax[tid] = 1.0f;
     for (int i = tid; i < 2 * NP * 32 * 16; i += 512) Px[i] = 0;
 
-    // partial scores of lane (row r16, position group g) go to exchange slot 4 r16 + (g ^ (r16 >> 2)): both the
-    // b128 writes and the owner's b128 reads (lane = 4 row + group) then touch 16 different chunks per 16 lanes
-    const int sx_put = (4 * r16 + (g ^ (r16 >> 2))) * 4;
-    const int sr = l >> 2, sq = l & 3;                                    // softmax lane = 4 * row + position group
-    const int sx_get = (4 * sr + (sq ^ (sr >> 2))) * 4;
-
-    // The pipeline of a piece whose tiles sit at list positions j .. j+npc-1, one barrier per step i = 0 .. npc+1:
-    //   score wavefronts   scores of tile j+i (i < npc) into exchange buffer (j+i)&1, and, between those MFMAs,
-    //                      the softmax of tile j+i-1 (1 <= i <= npc) from the other buffer into P buffer (j+i-1)&1;
-    //   sum wavefronts     request tile j+i+2 (i < npc); weighted sum of tile j+i-2 (2 <= i) from the column
-    //                      fragments they hold in registers and P buffer (j+i-2)&1, each fragment replaced, as soon
-    //                      as it is consumed, by the one of tile j+i-1 (1 <= i <= npc) read from its slot.
-    // So a tile's slot is read in two consecutive steps (scores, then column fragments) and is free afterwards:
-    // two tiles are resident and two in flight.  Both roles run npc + 2 barriers per piece.
+    // The pipeline over the span's tiles at list positions 0 .. nspan-1, one barrier per step i = 0 .. nspan+1;
+    // pieces follow each other without a gap:
+    //   score wavefronts   (i < nspan) partial scores of tile i into exchange buffer i&1; on an element's last tile
+    //                      each chunk of EL-Q is replaced, once its MFMAs are issued, by the next element's;
+    //                      (1 <= i <= nspan) softmax of tile i-1 from exchange buffer (i-1)&1 into P buffer (i-1)&1.
+    //   sum wavefronts     request tile i+3 (its slot was read last in step i-1); weighted sum of tile i-2 from the
+    //                      column fragments held in register set i&1 and P buffer i&1 (all zero while i < 2), each
+    //                      fragment replaced, once consumed, by the one of tile i (i < nspan); where tile i-2
+    //                      ends a piece, the piece is written out and the accumulators start afresh.
+    const int nsteps = nspan + 2;
     if (w < 4) {
         // =========================== score wavefront ===========================
-        const int rg = w / PARTS, part = w % PARTS;
-        const bool owner = part == 0;
+        const int part = w;
         int a_base[CHK];                                 // row r16, 16-byte chunk 4 (part CHK + c) + g of the row
         {
             const int fx = tile_swizzle(r16);
 #pragma unroll
             for (int c = 0; c < CHK; ++c) a_base[c] = r16 * ROWB + (((4 * (part * CHK + c) + g) ^ fx) << 4);
         }
-        // this wavefront's slice of EL-Q (high and low planes): B operand of the score product
-        u4 elq[CHK][2];
-        auto load_elq = [&](int b) {
-            const int row = row0 + 16 * rg + r16;
-            const size_t off = ((size_t)b * a.Rs + row) * DM + 32 * (part * CHK) + 8 * g;
+        // this wavefront's slice of EL-Q (all rows of the workgroup; high and low planes): B operand of the scores
+        u4 elq[CHK][RG][2];
+        auto load_elq_chunk = [&](int b, int c) {
 #pragma unroll
-            for (int c = 0; c < CHK; ++c) {
-                elq[c][0] = elq[c][1] = u4{0u, 0u, 0u, 0u};               // pad rows (>= R) are never written by a2
+            for (int rg = 0; rg < RG; ++rg) {
+                const int row = row0 + 16 * rg + r16;
+                const uint16_t *src = a.elq + elq_frag_index(b, row, 32 * (part * CHK + c) + 8 * g, 0, a.Rs, DM);
+                elq[c][rg][0] = elq[c][rg][1] = u4{0u, 0u, 0u, 0u};           // pad rows (>= R) are never written by a2
                 if (row < a.R) {
-                    elq[c][0] = *(const u4 *)(a.elq_hi + off + 32 * c);
-                    elq[c][1] = *(const u4 *)(a.elq_lo + off + 32 * c);
+                    elq[c][rg][0] = *(const u4 *)src;
+                    elq[c][rg][1] = *(const u4 *)(src + 512);
                 }
             }
         };
-        // Softmax bookkeeping of this row group for one tile (owner only), cut into twelve small stages that ride
-        // between the MFMAs of the next tile's scores (a stage is a few vector instructions: they issue while the
-        // matrix unit works, a longer run of them would hold the chain of MFMAs up).  Lane = 4 * row + q holds
-        // positions 4q..4q+3 of its row, so a row's statistics stay inside a quad.  Branch-free: a row whose
-        // maximum does not grow gets the factor exp2(0) = 1.
+        // exchange buffer: row stride 16 floats, 16-byte chunk c of row r at chunk position c ^ ((r >> 2) & 3)
+        int sx_put[RG];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) sx_put[rg] = part * SXP + (16 * rg + r16) * 16 + ((g ^ (r16 >> 2)) << 2);
+        // Softmax bookkeeping: this wavefront does rows part RPW .. part RPW + RPW - 1 of the workgroup; lane =
+        // LPR row + q holds positions TPL q .. TPL q + TPL - 1 of its row, so a row's statistics stay inside
+        // LPR neighbouring lanes (DPP).  Branch-free: a row whose maximum does not grow gets the factor exp2(0) = 1.
+        // It is cut into eight small stages that ride between the MFMAs of the next tile's scores: a stage is a few
+        // instructions, which issue while the matrix unit works; done in one piece, the chain of LDS round trips
+        // and dependent vector instructions would be waited for in full, every tile.
+        const int srow = part * RPW + l / LPR, t0 = TPL * (l % LPR);
+        const int sx_get = srow * 16 + (((t0 >> 2) ^ ((srow >> 2) & 3)) << 2) + (t0 & 3);
         float m_ref = -INFINITY, l_sum = 0.f;
-        f4 st[PARTS];
-        float sv[4], pr[4], alpha = 1.f, mx = 0.f;
-        unsigned ph[4], plo[4];
-        int sm_lim = 0;
-        auto sm_load = [&](int pos) {
-#pragma unroll
-            for (int p = 0; p < PARTS; ++p) st[p] = *(const f4 *)(Sx + (pos & 1) * 1024 + (rg * PARTS + p) * 256 + sx_get);
-        };
-        auto sm_sum = [&](int j) {                                    // sum of the partials of position 4q + j
-            float v = st[0][j];
-#pragma unroll
-            for (int p = 1; p < PARTS; ++p) v += st[p][j];
-            sv[j] = j < sm_lim ? v : -INFINITY;                         // positions at or beyond the length do not exist
-        };
-        auto sm_prob = [&](int j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; };
-        auto sm_split = [&](int j) {                                  // p = high + low, both bf16 by truncation
-            ph[j] = __float_as_uint(pr[j]) & 0xffff0000u;
-            plo[j] = __float_as_uint(pr[j] - __uint_as_float(ph[j]));
-        };
-        auto sm_stage = [&](int k, int pos) {
-            const int buf = pos & 1;
-            uint16_t *dst = Px + buf * (NP * 32 * 16) + (16 * rg + sr) * 16 + 4 * sq;
+        float sq[4][TPL], sv[TPL], pr[TPL], mx = 0.f, alpha = 1.f;
+        constexpr int NST = 8;
+        auto sm_stage = [&](int k, int pos, int lim) {
+            const float *sp = Sx + (pos & 1) * SXB + sx_get;
+            uint16_t *dst = Px + ((pos & 1) * NP * 32 + srow) * 16 + t0;
             switch (k) {
-            case 0: sm_sum(0); sm_sum(1); break;
-            case 1: sm_sum(2); sm_sum(3); break;
-            case 2: mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])); mx = fmaxf(mx, quad_xor1(mx)); break;
-            case 3: mx = fmaxf(mx, quad_xor2(mx)); break;
+            case 0:
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (TPL == 2) { const f2 o = *(const f2 *)(sp + q * SXP); sq[q][0] = o[0]; sq[q][TPL - 1] = o[1]; }
+                    else sq[q][0] = sp[q * SXP];
+                }
+                break;
+            case 1:
+#pragma unroll
+                for (int j = 0; j < TPL; ++j) {
+                    const float t = (sq[0][j] + sq[1][j]) + (sq[2][j] + sq[3][j]);
+                    sv[j] = t0 + j < lim ? t : -INFINITY;                 // positions at or beyond the length do not exist
+                }
+                mx = sv[0];
+                if (TPL == 2) mx = fmaxf(mx, sv[TPL - 1]);
+                break;
+            case 2: mx = fmaxf(mx, quad_xor1(mx)); mx = fmaxf(mx, quad_xor2(mx)); break;
+            case 3: mx = fmaxf(mx, dpp_half_mirror(mx)); if (LPR == 16) mx = fmaxf(mx, dpp_row_mirror(mx)); break;
             case 4: {
-                const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;    // also on a piece's first tile (m_ref = -inf)
-                // first tile: nothing accumulated yet, so no rescale (the factor 1 spares the pass over X)
+                // the reference maximum only advances when it would grow by more than the rescale step; a piece's
+                // first tile sets it (nothing is accumulated yet, so the factor 1 spares the pass over X)
+                const float m_new = mx > m_ref + kRescaleStep ? mx : m_ref;
                 alpha = m_ref == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
                 m_ref = m_new;
                 l_sum *= alpha;
                 break;
             }
-            case 5: sm_prob(0); sm_prob(1); break;
-            case 6: sm_prob(2); sm_prob(3); break;
-            case 7: if (BF16) { sm_split(0); sm_split(1); } break;
-            case 8: if (BF16) { sm_split(2); sm_split(3); } break;
-            case 9:
-                if (BF16) *(u2 *)dst = u2{(ph[0] >> 16) | ph[1], (ph[2] >> 16) | ph[3]};
-                else {
-                    const h2 p01 = __builtin_convertvector(f2{pr[0], pr[1]}, h2), p23 = __builtin_convertvector(f2{pr[2], pr[3]}, h2);
-                    *(h4 *)dst = h4{p01[0], p01[1], p23[0], p23[1]};
+            case 5:
+#pragma unroll
+                for (int j = 0; j < TPL; ++j) { pr[j] = __builtin_amdgcn_exp2f(sv[j] - m_ref); l_sum += pr[j]; }
+                break;
+            case 6:
+                if (BF16) {
+                    // p = high + low, both bf16 by truncation
+                    unsigned ph[TPL], plo[TPL];
+#pragma unroll
+                    for (int j = 0; j < TPL; ++j) {
+                        ph[j] = __float_as_uint(pr[j]) & 0xffff0000u;
+                        plo[j] = __float_as_uint(pr[j] - __uint_as_float(ph[j]));
+                    }
+                    if (TPL == 2) {
+                        *(unsigned *)dst = (ph[0] >> 16) | ph[TPL - 1];
+                        *(unsigned *)(dst + (NP - 1) * 32 * 16) = (plo[0] >> 16) | (plo[TPL - 1] & 0xffff0000u);
+                    } else {
+                        *dst = (uint16_t)(ph[0] >> 16);
+                        *(dst + (NP - 1) * 32 * 16) = (uint16_t)(plo[0] >> 16);
+                    }
+                } else {
+                    if (TPL == 2) *(h2 *)dst = __builtin_convertvector(f2{pr[0], pr[TPL - 1]}, h2);
+                    else *(f16_t *)dst = (f16_t)pr[0];
                 }
                 break;
-            case 10:
-                if (BF16) *(u2 *)(dst + 32 * 16) = u2{(plo[0] >> 16) | (plo[1] & 0xffff0000u), (plo[2] >> 16) | (plo[3] & 0xffff0000u)};
+            default:
+                if (l % LPR == 0) Ax[(pos & 1) * 32 + srow] = alpha;
                 break;
-            default: Ax[buf * 32 + 16 * rg + sr] = alpha; break;      // the four lanes of a quad write the same value
             }
         };
-        constexpr int NST = 12;
-        // scores of the tile at list position pos over this wavefront's columns, left in LDS for the exchange;
-        // with SM (owner only), the softmax of the tile before it rides between the MFMAs.  The fragment reads
-        // run PF chunks ahead of the MFMAs that use them.
-        auto scores = [&](int pos, auto sm_tag, int lim_rows) {
+        // where the tile at list position pos ends a piece: 1/sum for the sum wavefronts, the statistics for a6,
+        // and a fresh start
+        auto sm_close = [&](int pos, int b) {
+            float l_tot = l_sum;
+            l_tot += quad_xor1(l_tot);
+            l_tot += quad_xor2(l_tot);
+            l_tot += dpp_half_mirror(l_tot);
+            if (LPR == 16) l_tot += dpp_row_mirror(l_tot);
+            if (l % LPR == 0) {
+                Linv[(pos & 1) * 32 + srow] = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                if (row0 + srow < a.R) {
+                    float *ml_out = a.ML + ((size_t)(a.flat ? span + b : b) * a.Rs + row0 + srow) * 2;
+                    ml_out[0] = m_ref; ml_out[1] = l_tot;
+                }
+            }
+            m_ref = -INFINITY; l_sum = 0.f;
+        };
+        // partial scores of the tile at list position pos over this wavefront's columns; with SM, the softmax of the
+        // tile before it (whose `lim` first rows exist) rides between the MFMAs.  The fragment reads run PF chunks
+        // ahead of the MFMAs that use them; 2 RG independent chains of MFMAs.
+        auto scores = [&](int pos, auto reload_tag, int nb, auto sm_tag, int lim) {
+            constexpr bool RELOAD = decltype(reload_tag)::value;
             constexpr bool SM = decltype(sm_tag)::value;
             const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
             constexpr int PF = CHK < 4 ? CHK : 4;
-            if (SM) { sm_load(pos - 1); sm_lim = lim_rows - 4 * sq; }
             u4 hb[CHK];
 #pragma unroll
             for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
-            // two chains of MFMAs (high plane, low plane), so that no MFMA waits for the one issued just before it
-            f4 sc = f4{0.f, 0.f, 0.f, 0.f}, sc2 = f4{0.f, 0.f, 0.f, 0.f};
+            f4 sc[RG][2];
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) sc[rg][0] = sc[rg][1] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int c = 0; c < CHK; ++c) {
                 __builtin_amdgcn_sched_barrier(0);
                 if (c + PF < CHK) hb[c + PF] = *(const EL_LDS(u4) *)(F + a_base[c + PF]);
-                sc = Mma<BF16>::s16(hb[c], elq[c][0], sc);
-                if (SM) {
 #pragma unroll
-                    for (int k = 0; k < NST; ++k)
-                        if ((2 * k * CHK) / NST == 2 * c) sm_stage(k, pos - 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                sc2 = Mma<BF16>::s16(hb[c], elq[c][1], sc2);
-                if (SM) {
+                for (int pl = 0; pl < 2; ++pl) {
 #pragma unroll
-                    for (int k = 0; k < NST; ++k)
-                        if ((2 * k * CHK) / NST == 2 * c + 1) sm_stage(k, pos - 1);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            *(f4 *)(Sx + (pos & 1) * 1024 + w * 256 + sx_put) = f4{sc[0] + sc2[0], sc[1] + sc2[1], sc[2] + sc2[2], sc[3] + sc2[3]};
-        };
-
-        load_elq(b0);
-        int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
-        __syncthreads();                                              // the first two tiles have landed
-        for (int j = 0;;) {
-            const int ntile = (c_len + kTile - 1) / kTile;
-            const int npc = min(ntile - c_kt, nspan - j);                // tiles of this piece
-            const int rows0 = c_len - c_kt * kTile;                      // valid rows from the piece's first tile on
-            scores(j, std::false_type{}, 0);
-            __syncthreads();
-            for (int i = 1; i < npc; ++i) {
-                if (owner) scores(j + i, std::true_type{}, rows0 - (i - 1) * kTile);
-                else scores(j + i, std::false_type{}, 0);
-                __syncthreads();
-            }
-            j += npc;
-            const bool more = j < nspan;
-            // the next element's expanded queries are requested while this piece drains
-            if (more) load_elq(c_b + 1);
-            if (owner) {
-                // the softmax of the piece's last tile, then this row group's statistics
-                sm_load(j - 1); sm_lim = rows0 - (npc - 1) * kTile - 4 * sq;
+                    for (int rg = 0; rg < RG; ++rg) sc[rg][pl] = Mma<BF16>::s16(hb[c], elq[c][rg][pl], sc[rg][pl]);
+                    if (SM) {
 #pragma unroll
-                for (int k = 0; k < NST; ++k) sm_stage(k, j - 1);
-                l_sum += quad_xor1(l_sum);
-                l_sum += quad_xor2(l_sum);
-                const int row = row0 + 16 * rg + sr;
-                if (sq == 0) {
-                    Linv[16 * rg + sr] = l_sum > 0.f ? 1.0f / l_sum : 0.f;
-                    if (row < a.R) {
-                        float *ml_out = a.ML + ((size_t)(a.flat ? span + c_b : c_b) * a.Rs + row) * 2;
-                        ml_out[0] = m_ref; ml_out[1] = l_sum;
+                        for (int k = 0; k < NST; ++k)
+                            if ((k * 2 * CHK) / NST == 2 * c + pl) sm_stage(k, pos - 1, lim);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+                if (RELOAD) load_elq_chunk(nb, c);
             }
-            m_ref = -INFINITY; l_sum = 0.f;
-            __syncthreads();                                          // step npc: P of the last tile and 1/sum are in LDS
-            __syncthreads();                                          // step npc+1: the sum wavefronts finish the piece
-            if (!more) break;
-            ++c_b; c_kt = 0; c_len = elem_len(c_b);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg)
+                *(f4 *)(Sx + (pos & 1) * SXB + sx_put[rg]) = f4{sc[rg][0][0] + sc[rg][1][0], sc[rg][0][1] + sc[rg][1][1],
+                                                                 sc[rg][0][2] + sc[rg][1][2], sc[rg][0][3] + sc[rg][1][3]};
+        };
+
+#pragma unroll
+        for (int c = 0; c < CHK; ++c) load_elq_chunk(b0, c);
+        Cursor cs{b0, kt0, len0}, cq{b0, kt0, len0};                  // tile whose scores / whose softmax comes next
+        __syncthreads();                                              // the first tile has landed
+        for (int i = 0; i < nsteps; ++i) {
+            const bool sm = i >= 1 && i <= nspan;                         // the softmax of tile i - 1 belongs to this step
+            const int lim = cq.rows();
+            if (i < nspan) {
+                const bool reload = cs.elem_last() && i + 1 < nspan;
+                if (!sm) {                                                // the span's first tile: no softmax yet
+                    if (reload) scores(i, std::true_type{}, cs.b + 1, std::false_type{}, 0);
+                    else scores(i, std::false_type{}, 0, std::false_type{}, 0);
+                } else if (reload) scores(i, std::true_type{}, cs.b + 1, std::true_type{}, lim);
+                else scores(i, std::false_type{}, 0, std::true_type{}, lim);
+                advance(cs);
+            } else if (sm) {
+#pragma unroll
+                for (int k = 0; k < NST; ++k) sm_stage(k, i - 1, lim);
+            }
+            if (sm) {
+                if (cq.elem_last() || i == nspan) sm_close(i - 1, cq.b);
+                advance(cq);
+            }
+            __syncthreads();
         }
     } else {
         // =========================== sum wavefront ===========================
         const int v = w - 4;
-        const bool stream_hint = a.stream_hint != 0;
-        // fetch cursor: the tile that is requested next (two list positions ahead of the scores)
-        int f_b = b0, f_kt = kt0, f_len = elem_len(b0), f_pos = 0;
-        const char *f_H = (const char *)a.H + (size_t)b0 * a.h_stride * 2;
+        // fetch cursor: the tile that is requested next (three list positions ahead of the scores)
+        Cursor cf{b0, kt0, len0};
+        int f_pos = 0;
         // A sum wavefront fetches rows 4v..4v+3 of every tile, always with the same number of instructions: a
         // row that does not exist (at or beyond the element's length, or past the span) is replaced by a fetch
         // of the first row of H into a dump area, and, if the tile will be used, zeros are written in its place
         // (the slot is free when its fetch is requested).  The fetch counter then advances by exactly NI per tile.
+        // Everything a request needs is prepared once per tile (f_src, f_dst, f_rows), so that a request is a
+        // compare, two selects and the instruction itself.
         auto dma = [&](unsigned dst, unsigned voff, const char *sbase) {
-            if (PIECES == 2) { if (stream_hint) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
-            else { if (stream_hint) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
+            if (PIECES == 2) { if (NT) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
+            else { if (NT) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
         };
-        unsigned voff4[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) voff4[i] = (unsigned)(((l ^ ((i << 2) | v)) << 4) + i * ROWB);    // tile_swizzle(4v + i)
+        const unsigned lx = (unsigned)((l ^ v) << 4);                   // lane's chunk position before the row's part of the swizzle
+        const char *f_src;                                               // row 4v of the tile to request
+        unsigned f_dst;                                                  // where that row goes in LDS
+        int f_rows;                                                      // rows 4v.. of that tile that exist (<= 0: none)
+        auto fetch_setup = [&]() {
+            const bool live = f_pos < nspan;
+            f_rows = live ? cf.rows() - 4 * v : 0;
+            f_src = (const char *)a.H + ((size_t)min(cf.b, a.B - 1) * a.h_stride * 2 + ((size_t)cf.kt * kTile + 4 * v) * ROWB);
+            f_dst = t_lds + (f_pos & 3) * SLOT + 4 * v * ROWB;
+        };
         // the request of one tile, row by row, so that the weighted sum can spread the four requests over its MFMAs
         // (a request holds its wavefront up while the address unit is busy with the other wavefronts' requests)
         auto fetch_row = [&](int i) {
-            const int slot = f_pos & 3;
-            const bool live = f_pos < nspan;
-            const int rows = live ? f_len - f_kt * kTile : 0;          // valid rows of this tile (may exceed 16)
-            const int row = 4 * v + i;
-            const bool ok = row < rows;                                    // wave-uniform
-            const char *sbase = ok ? f_H + ((size_t)f_kt * kTile + 4 * v) * ROWB : (const char *)a.H - i * ROWB;
-            const unsigned dst = ok ? t_lds + slot * SLOT + row * ROWB : dz_lds;
-            dma(dst, voff4[i], sbase);
-            if (live && !ok) {
+            const bool ok = i < f_rows;                                    // wave-uniform
+            const unsigned voff = (lx ^ (unsigned)(i << 6)) + (ok ? i * ROWB : 0);     // tile_swizzle(4v + i) = 4i + v
+            dma(ok ? f_dst + i * ROWB : dz_lds, voff, ok ? f_src : (const char *)a.H);
+            if (!ok && f_pos < nspan) {
 #pragma unroll
-                for (int j = 0; j < PIECES; ++j) *(u4 *)(T + slot * SLOT + row * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
+                for (int j = 0; j < PIECES; ++j) *(u4 *)(T + (f_pos & 3) * SLOT + (4 * v + i) * ROWB + j * 1024 + l * 16) = u4{0u, 0u, 0u, 0u};
             }
         };
         auto fetch_advance = [&]() {
-            const bool live = f_pos < nspan;
+            if (f_pos < nspan) advance(cf);
             ++f_pos;
-            if (live) {
-                if (++f_kt * kTile >= f_len) {
-                    ++f_b; f_kt = 0;
-                    f_len = elem_len(f_b);
-                    f_H = (const char *)a.H + (size_t)min(f_b, a.B - 1) * a.h_stride * 2;
-                }
-            }
+            fetch_setup();
         };
         auto fetch_next = [&]() {
 #pragma unroll
             for (int i = 0; i < 4; ++i) fetch_row(i);
             fetch_advance();
         };
-        // wait until this wavefront's fetches of a tile have landed, given the tiles requested after it
-        auto wait_own = [&](int later_tiles) {
-            if (later_tiles >= 1) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NI) : "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        };
+        // wait until this wavefront's requests of a tile have landed while those of the two tiles after it are
+        // still in flight (requests return in order; stores of a piece that were issued meanwhile are waited
+        // for as well, which is more than needed but never less)
+        auto wait_tile = [&]() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NI) : "memory"); };
+
         int b_lo[4], b_hi[4];   // lane i = 4k+q of 16-lane block (dh, kg) reads row 8kg+k (+4), columns 32mb+16dh+4q..+3
         {
             const int dh = g & 1, k = r16 >> 2, q = r16 & 3;
@@ -422,56 +455,56 @@ k_core_stream(const StreamArgs a)
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
-        s4 tb[MB][2];                                    // column fragments of the tile whose weighted sum comes next
+        s4 tb[2][MB][2];                                 // column fragments of two tiles in flight between scores and sum
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) tb[s][mb][0] = tb[s][mb][1] = s4{0, 0, 0, 0};
+        const bool active = r32 < ROWS;
+        const int rowc = active ? r32 : 0;
 
-        // One step of the sum role: X^T[d, r] += sum_t H[t, d] P[r, t] for the tile whose fragments are held
-        // (do_pv; P and the factors from buffer pv_pos&1), each fragment replaced, once consumed, by the one of
-        // the tile at list position ld_pos (do_ld).
-        auto step = [&](bool do_pv, int pv_pos, bool do_ld, int ld_pos, bool do_fetch) {
-            const EL_LDS(char) *F = Tl + (ld_pos & 3) * SLOT;
+        // Step i of the sum role, register set SET = i & 1: X^T[d, r] += sum_t H[t, d] P[r, t] for tile i - 2 (whose
+        // fragments the set holds; P and the factors from buffer i & 1), each fragment replaced, once consumed,
+        // by the one of tile i (past the span's end: by whatever the slot holds, which is never used), and the
+        // requests of position i + 3 spread over the MFMAs.
+        auto step = [&](auto set_tag, int i) {
+            constexpr int SET = decltype(set_tag)::value;
+            const EL_LDS(char) *F = Tl + (i & 3) * SLOT;
             u4 P[NP];
-            float al = 1.f;
-            if (do_pv) {
-                const int buf = pv_pos & 1;
 #pragma unroll
-                for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + (buf * NP + pl) * (32 * 16) + r32 * 16 + 8 * kg);
-                al = Ax[buf * 32 + r32];
-                if (__any(al != 1.0f)) {
+            for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + ((SET * NP + pl) * 32 + r32) * 16 + 8 * kg);
+            const float al = Ax[SET * 32 + r32];
+            if (__any(al != 1.0f)) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) X[mb][i] *= al;
-                }
+                    for (int k = 0; k < 16; ++k) X[mb][k] *= al;
             }
             u4 hprev = u4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (do_pv) {
-                    // plane 0 of this block, then plane 1 of the block before it: no MFMA waits for its predecessor
-                    const s4 lo = tb[mb][0], hi = tb[mb][1];
-                    const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-                    X[mb] = Mma<BF16>::s32(hfrag, P[0], X[mb]);
-                    if (NP == 2 && mb > 0) X[mb - 1] = Mma<BF16>::s32(hprev, P[1], X[mb - 1]);
-                    hprev = hfrag;
-                }
-                if (do_ld) {
-                    tb[mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
-                    tb[mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
-                }
-                if (do_fetch && mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
+                // plane 0 of this block, then plane 1 of the block before it: no MFMA waits for its predecessor
+                const s4 lo = tb[SET][mb][0], hi = tb[SET][mb][1];
+                const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+                X[mb] = Mma<BF16>::s32(hfrag, P[0], X[mb]);
+                if (NP == 2 && mb > 0) X[mb - 1] = Mma<BF16>::s32(hprev, P[NP - 1], X[mb - 1]);
+                hprev = hfrag;
+                tb[SET][mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
+                tb[SET][mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
+                if (mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
             }
-            if (do_pv && NP == 2) X[MB - 1] = Mma<BF16>::s32(hprev, P[1], X[MB - 1]);
-            if (do_fetch) fetch_advance();
+            if (NP == 2) X[MB - 1] = Mma<BF16>::s32(hprev, P[NP - 1], X[MB - 1]);
+            fetch_advance();
             __builtin_amdgcn_sched_barrier(0);
         };
-        // close a piece: X normalised by its own sum, straight from the accumulators (a lane holds four
-        // consecutive columns of one row: 8-byte stores, two lanes side by side, four instructions fill 64 bytes
-        // of each of 32 rows)
-        auto store_piece = [&](int b) {
+        // close the piece whose last tile sat at list position pos: X normalised by its own sum, straight from the
+        // accumulators (a lane holds four consecutive columns of one row: 8-byte stores, two lanes side by side),
+        // and a fresh start for the next piece
+        auto close_piece = [&](int pos, int b) {
             const size_t slot = (size_t)(a.flat ? span + b : b);
-            const float inv = r32 < 16 * RG ? Linv[r32] : 0.f;
-            if (r32 < 16 * RG && row0 + r32 < a.R) {
+            const float inv = Linv[(pos & 1) * 32 + rowc];
+            if (active && row0 + r32 < a.R) {
                 f16_t *x_out = a.Xp + (slot * a.Rs + row0 + r32) * DM + DS * v + 4 * kg;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -485,35 +518,30 @@ k_core_stream(const StreamArgs a)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) X[mb][i] = 0.f;
+                for (int k = 0; k < 16; ++k) X[mb][k] = 0.f;
         };
 
+        fetch_setup();
         fetch_next();
         fetch_next();
-        int c_b = b0, c_kt = kt0, c_len = elem_len(b0);
-        wait_own(0);
-        __syncthreads();                                              // the first two tiles have landed
-        for (int j = 0;;) {
-            const int ntile = (c_len + kTile - 1) / kTile;
-            const int npc = min(ntile - c_kt, nspan - j);
-            for (int i = 0; i < npc; ++i) {
-                // list position j + i + 2 is requested in every step
-                if (i == 0) fetch_next();
-                if (i == 1) step(false, 0, true, j, true);
-                if (i >= 2) step(true, j + i - 2, true, j + i - 1, true);
-                wait_own(1);
-                __syncthreads();
+        fetch_next();
+        wait_tile();
+        __syncthreads();                                              // the first tile has landed
+        Cursor cp{b0, kt0, len0};                                     // the tile whose weighted sum comes next
+        auto one_step = [&](auto set_tag, int i) {
+            step(set_tag, i);
+            if (i >= 2) {
+                if (cp.elem_last() || i - 2 == nspan - 1) close_piece(i - 2, cp.b);
+                advance(cp);
             }
-            j += npc;
-            if (npc >= 2) step(true, j - 2, true, j - 1, false);      // step npc
-            else step(false, 0, true, j - 1, false);
+            wait_tile();
             __syncthreads();
-            step(true, j - 1, false, 0, false);                       // step npc + 1
-            store_piece(c_b);
-            __syncthreads();
-            if (j >= nspan) break;
-            ++c_b; c_kt = 0; c_len = elem_len(c_b);
+        };
+        for (int i = 0; i < nsteps; i += 2) {
+            one_step(std::integral_constant<int, 0>{}, i);
+            if (i + 1 < nsteps) one_step(std::integral_constant<int, 1>{}, i + 1);
         }
+        // the last requests went to the dump area; none may be in flight when the workgroup gives up its LDS
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 }
@@ -521,19 +549,20 @@ k_core_stream(const StreamArgs a)
 // ---------------------------------------------------------------------------------------------
 // With a pair of events the launch carries them itself (they then read the dispatch's own begin and end,
 // without the command-processor time a separately recorded event adds on either side).
-template <int DM, bool BF16, int RG>
+template <int DM, bool BF16, int RG, bool NT>
 static void launch_one(const StreamArgs &a, dim3 grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
-    if (ev0 && ev1) hipExtLaunchKernelGGL((k_core_stream<DM, BF16, RG>), grid, dim3(512), 0, s, ev0, ev1, 0, a);
-    else hipLaunchKernelGGL((k_core_stream<DM, BF16, RG>), grid, dim3(512), 0, s, a);
+    if (ev0 && ev1) hipExtLaunchKernelGGL((k_core_stream<DM, BF16, RG, NT>), grid, dim3(512), 0, s, ev0, ev1, 0, a);
+    else hipLaunchKernelGGL((k_core_stream<DM, BF16, RG, NT>), grid, dim3(512), 0, s, a);
 }
 
 template <int DM, bool BF16>
 static hipError_t launch_t(const StreamArgs &a, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1)
 {
     const dim3 grid(((a.G * a.nblocks + 7) / 8) * 8);
-    if (rg == 1) launch_one<DM, BF16, 1>(a, grid, s, ev0, ev1);
-    else launch_one<DM, BF16, 2>(a, grid, s, ev0, ev1);
+    const bool nt = a.stream_hint != 0;
+    if (rg == 1) { if (nt) launch_one<DM, BF16, 1, true>(a, grid, s, ev0, ev1); else launch_one<DM, BF16, 1, false>(a, grid, s, ev0, ev1); }
+    else { if (nt) launch_one<DM, BF16, 2, true>(a, grid, s, ev0, ev1); else launch_one<DM, BF16, 2, false>(a, grid, s, ev0, ev1); }
     return hipGetLastError();
 }
 

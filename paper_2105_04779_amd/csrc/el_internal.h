@@ -78,6 +78,17 @@ __device__ __forceinline__ void dma_row_2k_nt(unsigned lds_addr, unsigned voff, 
 static inline size_t dtype_size(int dt) { return dt == EL_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// EL-Q for the MFMA core is stored in the order its score wavefronts load it: 1 KB fragments of 16 rows x 32
+// columns (row-major inside: element (r16, c32) at r16 * 32 + c32), ordered [batch element][row / 16][column / 32]
+// [plane: 0 high, 1 low], so that one load instruction of a wavefront (lane = 4 r16 + column group) reads one
+// contiguous fragment.  Returns the element index of (b, row, col) of a plane; Rs = padded row count, a multiple
+// of 16.
+__host__ __device__ __forceinline__ size_t elq_frag_index(int b, int row, int col, int plane, int Rs, int d_m)
+{
+    const size_t frag = (((size_t)b * (Rs >> 4) + (row >> 4)) * (d_m >> 5) + (col >> 5)) * 2 + plane;
+    return frag * 512 + (size_t)(row & 15) * 32 + (col & 31);
+}
+
 // ---- compile-time limits -----------------------------------------------------------------
 constexpr int kMaxParts = 8;        // key-range partials per (batch element, row) the workspace holds
 constexpr int kGenericMaxDm = 8192; // widest d_model the generic core kernel covers
@@ -205,8 +216,8 @@ struct StreamArgs {
     const void *H;
     int64_t h_stride;        // elements between batch elements
     const int32_t *lengths;
-    const uint16_t *elq_hi;  // [B, Rs, DM] high and low 16-bit planes of EL-Q in the storage type,
-    const uint16_t *elq_lo;  //   scaled by log2(e)/sqrt(d_k)
+    const uint16_t *elq;     // EL-Q as high + low 16-bit planes in the storage type, scaled by log2(e)/sqrt(d_k),
+                             //   in fragment order (see elq_frag_index)
     f16_t *Xp;               // [slot, Rs, DM] fp16, each piece already divided by its own sum
     float *ML;               // [slot, Rs, 2]  (reference max in log2 units, sum)
     int32_t *E;              // [B+1] prefix sum of tile counts (flat cut), written by the kernel; may be null

@@ -40,8 +40,7 @@ struct GemmArgs {
     int M, N, K;          // per batch (head)
     int lda, ldb, ldc;    // row strides in elements
     int x;                // beam: logical row m = b*x + j
-    int c_rB;             // k_elq_slab: output row of logical row m, head i = (m / x) * c_rB + i * x + m % x
-    void *C2;             // k_elq_slab: the low plane
+    int c_rB;             // k_elq_slab: padded rows per batch element of the output (logical row m, head i -> row i * x + m % x of element m / x)
     // k_vproj_slab: A points at the normalised fp16 pieces Xp [slot, Rs, d_m]; ML [slot, Rs, 2]; pm says which
     // slots belong to a batch element, parts bounds their number
     const float *ML;
@@ -355,7 +354,8 @@ hipError_t launch_transpose16(const void *src, void *dst, int rows, int cols, hi
 // of W^K (64 x 64, 8 KB) is read once and stays in registers as MFMA fragments while the four
 // wavefronts walk over the row tiles, so W^K is read once per 256 rows instead of once per 16.
 // Weights are the MFMA's A operand: a lane ends up with four consecutive columns of one row; the
-// 16 x 64 tile then goes through LDS and leaves as whole 128-byte lines.
+// 16 x 64 tile then goes through LDS and leaves in the fragment order of the attention core (elq_frag_index),
+// 64 contiguous bytes per row and 32-column fragment.
 template <bool BF>
 __global__ void __launch_bounds__(256)
 k_elq_slab(const GemmArgs g)
@@ -408,9 +408,9 @@ k_elq_slab(const GemmArgs g)
         for (int hf = 0; hf < 2; ++hf) {
             const int row = 8 * hf + (l >> 3), m = (mt0 + w + 4 * mi) * 16 + row;
             if (m >= g.M) continue;
-            const size_t c_row = (size_t)(m / g.x) * g.c_rB + (size_t)(m % g.x) + (size_t)head * g.x;
-            *(u4 *)((uint16_t *)g.C + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const u4 *)(&Ct[0][w][mi][row * 72 + 8 * (l & 7)]);
-            *(u4 *)((uint16_t *)g.C2 + c_row * g.ldc + n0 + 8 * (l & 7)) = *(const u4 *)(&Ct[1][w][mi][row * 72 + 8 * (l & 7)]);
+            uint16_t *dst = (uint16_t *)g.C + elq_frag_index(m / g.x, head * g.x + m % g.x, n0 + 8 * (l & 7), 0, g.c_rB, g.ldc);
+            *(u4 *)dst = *(const u4 *)(&Ct[0][w][mi][row * 72 + 8 * (l & 7)]);
+            *(u4 *)(dst + 512) = *(const u4 *)(&Ct[1][w][mi][row * 72 + 8 * (l & 7)]);
         }
     }
 }
@@ -445,11 +445,11 @@ hipError_t launch_qproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     return p.dtype == EL_BF16 ? launch_slab<true, C_F16>(g, s) : launch_slab<false, C_F16>(g, s);
 }
 
-// a2: ELQ[b, i*beam+j, :] = Qp[b*beam+j, head i] . (W_i^K)^T      fp16, row stride d_m, Rs rows per b
+// a2: ELQ[b, i*beam+j, :] = Qp[b*beam+j, head i] . (W_i^K)^T      high + low planes in fragment order, Rs rows per b
 hipError_t launch_elq_mfma(const el_attn_ctx *ctx, const Problem &p, const Workspace &ws, int Rs, hipStream_t s)
 {
     GemmArgs g = base_args(p);
-    g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ; g.C2 = (uint16_t *)ws.ELQ + (size_t)p.B * Rs * p.d_m;
+    g.A = ws.Qp; g.Bt = ctx->w.WkH; g.C = ws.ELQ;
     g.N = p.d_m; g.K = p.d_k; g.lda = p.hd; g.ldb = p.hd; g.ldc = p.d_m;
     g.c_rB = Rs;
     const dim3 grid(p.d_m / 64, p.heads, (g.M + 255) / 256);

@@ -112,18 +112,20 @@ def test_plan_preview_on_the_benchmark_shapes(ea):
         st, rg, sp = ea.el_attn_plan_preview(B, beam, heads, d_m, n, 256)
         assert st == ea.EL_OK
         return rg, sp
-    assert plan(64, 4, 16, 1024, 1024) == (4, 4)     # 64 sentences x 4 beams, long inputs: all rows, four key ranges
-    assert plan(320, 4, 16, 1024, 1024) == (4, 2)    # 320 sentences: two ranges, 2.5 rounds of workgroups
-    assert plan(512, 1, 16, 1024, 1024) == (1, 1)    # per-beam histories: 16 rows, no cut
-    assert plan(64, 4, 16, 1024, 256) == (2, 2)      # short inputs: half the rows per workgroup instead of more cuts
-    rg, sp = plan(64, 4, 16, 1024, 64)
-    assert sp == 1 and rg in (1, 2)                  # four tiles: never cut
+    # rows per workgroup in 16s, spans of the flattened tile list (workgroups = spans x row blocks)
+    assert plan(64, 4, 16, 1024, 1024) == (2, 128)   # 64 rows: two blocks of 32, one workgroup per compute unit
+    assert plan(320, 4, 16, 1024, 1024) == (2, 128)  # more sentences: longer spans, never more workgroups than units
+    assert plan(512, 1, 16, 1024, 1024) == (1, 256)  # per-beam histories: 16 rows, one block
+    assert plan(64, 4, 16, 1024, 256) == (2, 128)    # 1024 tiles: still eight per span
+    assert plan(64, 4, 16, 1024, 64) == (2, 32)      # four tiles per sentence: spans of at least eight tiles
+    assert plan(2, 4, 16, 1024, 16) == (2, 1)        # two tiles in all
     for B in (1, 3, 17, 64, 100, 1000):
         for beam in (1, 2, 4, 5, 8):
             for n in (1, 16, 100, 1024, 4096):
                 rg, sp = plan(B, beam, 16, 1024, n)
-                assert rg in (1, 2, 4) and 1 <= sp <= ea.el_attn_max_splits()
-                assert rg <= {1: 1, 2: 2}.get(beam, 4)             # never more rows than the shape has (in 16s, padded)
+                blocks = -(-16 * beam // (16 * rg))
+                assert rg == (1 if beam == 1 else 2) and 1 <= sp and sp * blocks <= max(256, blocks)
+                assert sp <= B * (ea.el_attn_max_splits() - 1)             # every piece has a slot
     I = ea.EL_ERR_INVALID_ARG
     assert ea.el_attn_plan_preview(0, 4, 16, 1024, 64, 256)[0] == I
     assert ea.el_attn_plan_preview(4, 4, 16, 1024, 64, 0)[0] == I
