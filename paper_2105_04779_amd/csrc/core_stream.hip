@@ -57,6 +57,7 @@ namespace {
 
 constexpr int kTile = 16;                 // rows of H per tile
 constexpr float kRescaleStep = 10.0f;     // log2 units: probabilities stay below 2^10
+constexpr float kMasked = -1.0e30f;       // score of a position that does not exist: finite, exp2 of it is 0
 
 // chunk swizzle of a 16-row tile: the two bit pairs of the row number swapped.  A bijection on
 // four bits (row-wise b128 reads of 16 rows hit 16 different chunk positions) whose upper pair
@@ -217,16 +218,29 @@ k_core_stream(const StreamArgs a)
             for (int c = 0; c < CHK; ++c) a_base[c] = r16 * ROWB + (((4 * (part * CHK + c) + g) ^ fx) << 4);
         }
         // this wavefront's slice of EL-Q (all rows of the workgroup; high and low planes): B operand of the scores
+        // (fragment order: chunk c of row group rg lies 2 KB after chunk c - 1, its low plane 1 KB after the high
+        // one, so one 64-bit base per batch element and compile-time offsets address everything)
         u4 elq[CHK][RG][2];
-        auto load_elq_chunk = [&](int b, int c) {
+        const unsigned elq_lane = (unsigned)(elq_frag_index(0, row0 + r16, 32 * (part * CHK) + 8 * g, 0, a.Rs, DM) * 2);   // bytes
+        const size_t elq_elem = (size_t)a.Rs * DM * 4;                     // bytes of one batch element (two planes)
+        constexpr int kRgStep = (DM / 32) * 2048;                           // bytes between row groups
+        // pad rows (>= R) are never written by a2: their lanes keep the zeros they start with (a lane always holds
+        // the same rows, so loads under this predicate never touch them)
+        bool row_ok[RG];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) row_ok[rg] = row0 + 16 * rg + r16 < a.R;
+#pragma unroll
+        for (int c = 0; c < CHK; ++c)
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) elq[c][rg][0] = elq[c][rg][1] = u4{0u, 0u, 0u, 0u};
+        const char *elq_src = nullptr;                                     // this lane's first fragment of the element being loaded
+        auto elq_begin = [&](int b) { elq_src = (const char *)a.elq + (size_t)b * elq_elem + elq_lane; };
+        auto load_elq_chunk = [&](int c) {
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
-                const int row = row0 + 16 * rg + r16;
-                const uint16_t *src = a.elq + elq_frag_index(b, row, 32 * (part * CHK + c) + 8 * g, 0, a.Rs, DM);
-                elq[c][rg][0] = elq[c][rg][1] = u4{0u, 0u, 0u, 0u};           // pad rows (>= R) are never written by a2
-                if (row < a.R) {
-                    elq[c][rg][0] = *(const u4 *)src;
-                    elq[c][rg][1] = *(const u4 *)(src + 512);
+                if (row_ok[rg]) {
+                    elq[c][rg][0] = *(const u4 *)(elq_src + rg * kRgStep + c * 2048);
+                    elq[c][rg][1] = *(const u4 *)(elq_src + rg * kRgStep + c * 2048 + 1024);
                 }
             }
         };
@@ -260,7 +274,7 @@ k_core_stream(const StreamArgs a)
 #pragma unroll
                 for (int j = 0; j < TPL; ++j) {
                     const float t = (sq[0][j] + sq[1][j]) + (sq[2][j] + sq[3][j]);
-                    sv[j] = t0 + j < lim ? t : -INFINITY;                 // positions at or beyond the length do not exist
+                    sv[j] = t0 + j < lim ? t : kMasked;                   // positions at or beyond the length do not exist
                 }
                 mx = sv[0];
                 if (TPL == 2) mx = fmaxf(mx, sv[TPL - 1]);
@@ -323,14 +337,17 @@ k_core_stream(const StreamArgs a)
             }
             m_ref = -INFINITY; l_sum = 0.f;
         };
-        // partial scores of the tile at list position pos over this wavefront's columns; with SM, the softmax of the
-        // tile before it (whose `lim` first rows exist) rides between the MFMAs.  The fragment reads run PF chunks
-        // ahead of the MFMAs that use them; 2 RG independent chains of MFMAs.
-        auto scores = [&](int pos, auto reload_tag, int nb, auto sm_tag, int lim) {
+        // partial scores of the tile at list position pos over this wavefront's columns; the softmax of the tile
+        // before it (whose `lim` first rows exist) rides between the MFMAs.  The fragment reads run PF chunks
+        // ahead of the MFMAs that use them; 2 RG independent chains of MFMAs.  There is one copy of this code
+        // per RELOAD value and no more: further copies that redefine the EL-Q registers make the compiler spill
+        // them.  The span's first tile therefore runs the stages too, on no positions (lim = 0): finite
+        // probabilities that meet zero fragments, and statistics that are reset afterwards.
+        auto scores = [&](int pos, auto reload_tag, int nb, int lim) {
             constexpr bool RELOAD = decltype(reload_tag)::value;
-            constexpr bool SM = decltype(sm_tag)::value;
             const EL_LDS(char) *F = Tl + (pos & 3) * SLOT;
             constexpr int PF = CHK < 4 ? CHK : 4;
+            if (RELOAD) elq_begin(nb);
             u4 hb[CHK];
 #pragma unroll
             for (int c = 0; c < PF; ++c) hb[c] = *(const EL_LDS(u4) *)(F + a_base[c]);
@@ -345,14 +362,12 @@ k_core_stream(const StreamArgs a)
                 for (int pl = 0; pl < 2; ++pl) {
 #pragma unroll
                     for (int rg = 0; rg < RG; ++rg) sc[rg][pl] = Mma<BF16>::s16(hb[c], elq[c][rg][pl], sc[rg][pl]);
-                    if (SM) {
 #pragma unroll
-                        for (int k = 0; k < NST; ++k)
-                            if ((k * 2 * CHK) / NST == 2 * c + pl) sm_stage(k, pos - 1, lim);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+                    for (int k = 0; k < NST; ++k)
+                        if ((k * 2 * CHK) / NST == 2 * c + pl) sm_stage(k, pos - 1, lim);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (RELOAD) load_elq_chunk(nb, c);
+                if (RELOAD) load_elq_chunk(c);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -361,8 +376,9 @@ k_core_stream(const StreamArgs a)
                                                                  sc[rg][0][2] + sc[rg][1][2], sc[rg][0][3] + sc[rg][1][3]};
         };
 
+        elq_begin(b0);
 #pragma unroll
-        for (int c = 0; c < CHK; ++c) load_elq_chunk(b0, c);
+        for (int c = 0; c < CHK; ++c) load_elq_chunk(c);
         Cursor cs{b0, kt0, len0}, cq{b0, kt0, len0};                  // tile whose scores / whose softmax comes next
         __syncthreads();                                              // the first tile has landed
         for (int i = 0; i < nsteps; ++i) {
@@ -370,11 +386,9 @@ k_core_stream(const StreamArgs a)
             const int lim = cq.rows();
             if (i < nspan) {
                 const bool reload = cs.elem_last() && i + 1 < nspan;
-                if (!sm) {                                                // the span's first tile: no softmax yet
-                    if (reload) scores(i, std::true_type{}, cs.b + 1, std::false_type{}, 0);
-                    else scores(i, std::false_type{}, 0, std::false_type{}, 0);
-                } else if (reload) scores(i, std::true_type{}, cs.b + 1, std::true_type{}, lim);
-                else scores(i, std::false_type{}, 0, std::true_type{}, lim);
+                if (reload) scores(i, std::true_type{}, cs.b + 1, sm ? lim : 0);
+                else scores(i, std::false_type{}, 0, sm ? lim : 0);
+                if (!sm) { m_ref = -INFINITY; l_sum = 0.f; }
                 advance(cs);
             } else if (sm) {
 #pragma unroll
@@ -467,13 +481,14 @@ k_core_stream(const StreamArgs a)
         // fragments the set holds; P and the factors from buffer i & 1), each fragment replaced, once consumed,
         // by the one of tile i (past the span's end: by whatever the slot holds, which is never used), and the
         // requests of position i + 3 spread over the MFMAs.
-        auto step = [&](auto set_tag, int i) {
+        auto step = [&](auto set_tag, int i, auto &&bookkeeping) {
             constexpr int SET = decltype(set_tag)::value;
             const EL_LDS(char) *F = Tl + (i & 3) * SLOT;
             u4 P[NP];
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl) P[pl] = *(const u4 *)(Px + ((SET * NP + pl) * 32 + r32) * 16 + 8 * kg);
             const float al = Ax[SET * 32 + r32];
+            bookkeeping();                                                // scalar work while the reads are on their way
             if (__any(al != 1.0f)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -504,17 +519,25 @@ k_core_stream(const StreamArgs a)
         auto close_piece = [&](int pos, int b) {
             const size_t slot = (size_t)(a.flat ? span + b : b);
             const float inv = Linv[(pos & 1) * 32 + rowc];
-            if (active && row0 + r32 < a.R) {
-                f16_t *x_out = a.Xp + (slot * a.Rs + row0 + r32) * DM + DS * v + 4 * kg;
+            // A lane holds columns 8 q4 + 4 kg .. + 3 of every 32-column block of its row.  The two lanes of a row
+            // trade neighbouring groups (v_permlane32_swap), so that each holds eight consecutive columns and a
+            // store instruction writes 32 contiguous bytes of each row instead of two pieces of 8.
+            const bool keep = active && row0 + r32 < a.R;
+            f16_t *x_out = a.Xp + (slot * a.Rs + row0 + rowc) * DM + DS * v + 8 * kg;
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const h2 lo = __builtin_convertvector(f2{X[mb][4 * q4 + 0] * inv, X[mb][4 * q4 + 1] * inv}, h2);
-                        const h2 hi = __builtin_convertvector(f2{X[mb][4 * q4 + 2] * inv, X[mb][4 * q4 + 3] * inv}, h2);
-                        *(h4 *)(x_out + 32 * mb + 8 * q4) = h4{lo[0], lo[1], hi[0], hi[1]};
+                for (int qp = 0; qp < 2; ++qp) {
+                    unsigned ga[2], gb[2];                                   // groups q4 = 2 qp and 2 qp + 1, two fp16 pairs each
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        ga[h] = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{X[mb][8 * qp + 2 * h] * inv, X[mb][8 * qp + 2 * h + 1] * inv}, h2));
+                        gb[h] = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{X[mb][8 * qp + 4 + 2 * h] * inv, X[mb][8 * qp + 4 + 2 * h + 1] * inv}, h2));
+                        const auto sw = __builtin_amdgcn_permlane32_swap(ga[h], gb[h], false, false);
+                        ga[h] = sw[0]; gb[h] = sw[1];
                     }
-            }
+                    if (keep) *(u4 *)(x_out + 32 * mb + 16 * qp) = u4{ga[0], ga[1], gb[0], gb[1]};
+                }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -529,11 +552,16 @@ k_core_stream(const StreamArgs a)
         __syncthreads();                                              // the first tile has landed
         Cursor cp{b0, kt0, len0};                                     // the tile whose weighted sum comes next
         auto one_step = [&](auto set_tag, int i) {
-            step(set_tag, i);
-            if (i >= 2) {
-                if (cp.elem_last() || i - 2 == nspan - 1) close_piece(i - 2, cp.b);
-                advance(cp);
-            }
+            bool closes = false;
+            int close_b = 0;
+            step(set_tag, i, [&]() {
+                if (i >= 2) {
+                    closes = cp.elem_last() || i - 2 == nspan - 1;
+                    close_b = cp.b;
+                    advance(cp);
+                }
+            });
+            if (closes) close_piece(i - 2, close_b);
             wait_tile();
             __syncthreads();
         };
