@@ -131,10 +131,11 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML; a.E = pl.flat ? ws.E : nullptr;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.nblocks = pl.nblocks;
     a.flat = pl.flat; a.G = pl.G; a.lfloor = pl.lfloor;
-    // H is read once per step; when a batch of it is large against the 256 MB memory-side cache, keeping its
-    // lines out of the caches leaves them to the data that is re-read and raises the streaming rate (measured:
-    // 5.3 -> 6.2 TB/s on 1 GB of per-beam histories; 0.5 us per step at 128 MB; slower on a 25 MB batch)
-    a.stream_hint = (double)p.B * p.n * p.d_m * 2.0 >= 128.0 * 1024 * 1024 ? 1 : 0;
+    // H is read once per step; when a batch of it is larger than the 256 MB memory-side cache, keeping its lines
+    // out of the caches leaves them to the data that is re-read and raises the streaming rate (measured, core
+    // kernel: 1 GB of per-beam histories 216 -> 184 us; 640 MB shared by two row blocks 149 -> 144 us).  Below
+    // that it costs: the second row block of a span then misses what the first one fetched (128 MB: 42.7 -> 44.6 us).
+    a.stream_hint = (double)p.B * p.n * p.d_m * 2.0 >= 256.0 * 1024 * 1024 ? 1 : 0;
     return launch_core_stream(a, p.d_m, p.dtype == EL_BF16, pl.nrg, s, ev0, ev1);
 }
 
