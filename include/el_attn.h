@@ -130,8 +130,17 @@ el_status el_attn_bind_workspace(el_attn_ctx *ctx, void *dev_ptr, size_t bytes);
  * beam := 1 (section 3.1.1: the state is the previous layer's output, appended
  * by the caller before the call).
  *
+ * Alignment: where el_attn_uses_mfma(ctx) is 1 the kernels move operands in
+ * 16-byte pieces, so H, queries and out must be 16-byte aligned and
+ * H_batch_stride * sizeof(element) a multiple of 16 (d_model is 512 or 1024
+ * there, so rows are); on the generic path element alignment suffices.
+ * lengths must be 4-byte aligned.  A violation is INVALID_ARG, found on the host
+ * before any device work.  el_attn_decode_segment and el_attn_merge_segments
+ * apply the same rules to their operands (their fp32 buffers: 4 bytes).
+ *
  * Errors: INVALID_ARG (null ctx/H/queries/out; B, beam or n < 1 or beyond the
- * prepared maxima; H_batch_stride < n*d_model), WORKSPACE, HIP (launch failure).
+ * prepared maxima; H_batch_stride < n*d_model; misaligned operands),
+ * WORKSPACE, HIP (launch failure).
  */
 el_status el_attn_decode_step(el_attn_ctx *ctx,
                               const void *H, int64_t H_batch_stride,
@@ -227,6 +236,19 @@ el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups);
  */
 el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,
                                int32_t compute_units, int32_t *row_groups, int32_t *spans);
+
+/*
+ * The operand checks of el_attn_decode_step (shapes against the configured maxima, strides, and the
+ * alignment rules stated there) as host arithmetic on a configuration alone: no context, no device, no
+ * pointer is dereferenced.  `mfma` says which path's rules apply (what el_attn_uses_mfma would return
+ * for a context prepared from `cfg`).  Returns EL_OK, INVALID_ARG as decode_step would, or UNSUPPORTED
+ * if `mfma` is nonzero for a (dtype, d_model) the MFMA kernels do not cover.  For callers that want to
+ * validate buffers when they allocate them rather than on the first step.
+ */
+el_status el_attn_check_step_operands(const el_attn_config *cfg, int32_t mfma,
+                                      const void *H, int64_t H_batch_stride, const int32_t *lengths,
+                                      const void *queries, const void *out,
+                                      int32_t B, int32_t beam, int32_t n);
 
 /* 1 if decode_step on this context runs the MFMA kernels, 0 if the generic fp32 ones. */
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx);

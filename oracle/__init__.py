@@ -32,22 +32,25 @@ _lock = threading.Lock()
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile mha_oracle.c into libmha_oracle.so next to it (gcc, OpenMP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC",
+def build(force: bool = False, out: str | None = None, extra_flags=()) -> str:
+    """Compile mha_oracle.c into libmha_oracle.so next to it (gcc, OpenMP).  With `out`, into that file
+    instead, with `extra_flags` added (the sanitizer test builds an instrumented copy this way)."""
+    lib = out or _LIB
+    if force or out or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC", *extra_flags,
                "-o", tmp, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, lib)
+    return lib
 
 
 def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
+            # MHA_ORACLE_LIB: a library built by build(out=...) to load instead (same source, other compiler flags)
+            lib = ctypes.CDLL(os.environ.get("MHA_ORACLE_LIB") or build())
             dp = ctypes.POINTER(ctypes.c_double)
             ip = ctypes.POINTER(ctypes.c_int32)
             sig = [ctypes.c_int] * 6 + [dp, ip, dp] + [dp] * 8 + [dp]

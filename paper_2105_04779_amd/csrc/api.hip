@@ -78,12 +78,44 @@ int auto_parts_generic(const Problem &p)
     return parts < 1 ? 1 : parts;
 }
 
+bool aligned_to(const void *p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Element alignment for every path; on the MFMA path operands are fetched and stored in 16-byte pieces.
+uintptr_t operand_alignment(const el_attn_config &cfg, bool mfma) { return mfma ? 16 : dtype_size(cfg.dtype); }
+
+// The shape and alignment rules of the queries (every call that takes them) ...
+el_status check_queries(const el_attn_config &cfg, bool mfma, const void *queries, int32_t B, int32_t beam)
+{
+    if (!queries) return EL_ERR_INVALID_ARG;
+    if (B < 1 || beam < 1) return EL_ERR_INVALID_ARG;
+    if (B > cfg.max_batch || beam > cfg.max_beam) return EL_ERR_INVALID_ARG;
+    if (!aligned_to(queries, operand_alignment(cfg, mfma))) return EL_ERR_INVALID_ARG;
+    return EL_OK;
+}
+
+// ... and of the hidden states and their lengths
+el_status check_hidden(const el_attn_config &cfg, bool mfma, const void *H, int64_t H_batch_stride, const int32_t *lengths, int32_t n)
+{
+    if (!H) return EL_ERR_INVALID_ARG;
+    if (n < 1 || n > cfg.max_n) return EL_ERR_INVALID_ARG;
+    if (H_batch_stride < (int64_t)n * cfg.d_model) return EL_ERR_INVALID_ARG;
+    const uintptr_t al = operand_alignment(cfg, mfma);
+    if (!aligned_to(H, al)) return EL_ERR_INVALID_ARG;
+    if (((uint64_t)H_batch_stride * dtype_size(cfg.dtype)) % al != 0) return EL_ERR_INVALID_ARG;
+    if (lengths && !aligned_to(lengths, sizeof(int32_t))) return EL_ERR_INVALID_ARG;
+    return EL_OK;
+}
+
+el_status check_out(const el_attn_config &cfg, bool mfma, const void *out)
+{
+    if (!out) return EL_ERR_INVALID_ARG;
+    return aligned_to(out, mfma ? 16 : dtype_size(cfg.out_dtype)) ? EL_OK : EL_ERR_INVALID_ARG;
+}
+
 el_status check_step_args(const el_attn_ctx *ctx, const void *queries, int32_t B, int32_t beam)
 {
-    if (!ctx || !queries) return EL_ERR_INVALID_ARG;
-    if (B < 1 || beam < 1) return EL_ERR_INVALID_ARG;
-    if (B > ctx->cfg.max_batch || beam > ctx->cfg.max_beam) return EL_ERR_INVALID_ARG;
-    return EL_OK;
+    if (!ctx) return EL_ERR_INVALID_ARG;
+    return check_queries(ctx->cfg, el_attn_uses_mfma(ctx) != 0, queries, B, beam);
 }
 
 Problem make_problem(const el_attn_ctx *ctx, const void *H, int64_t stride, const int32_t *lengths,
@@ -163,11 +195,10 @@ el_status run_a7(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, const 
     return e == hipSuccess ? EL_OK : EL_ERR_HIP;
 }
 
-el_status check_keys(const el_attn_ctx *ctx, const void *H, int64_t H_batch_stride, int32_t n)
+el_status check_keys(const el_attn_ctx *ctx, const void *H, int64_t H_batch_stride, const int32_t *lengths, int32_t n)
 {
-    if (!H) return EL_ERR_INVALID_ARG;
-    if (n < 1 || n > ctx->cfg.max_n) return EL_ERR_INVALID_ARG;
-    if (H_batch_stride < (int64_t)n * ctx->cfg.d_model) return EL_ERR_INVALID_ARG;
+    const el_status st = check_hidden(ctx->cfg, el_attn_uses_mfma(ctx) != 0, H, H_batch_stride, lengths, n);
+    if (st != EL_OK) return st;
     if (!ctx->ws_base) return EL_ERR_WORKSPACE;
     return EL_OK;
 }
@@ -311,6 +342,18 @@ el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d
     return EL_OK;
 }
 
+el_status el_attn_check_step_operands(const el_attn_config *cfg, int32_t mfma, const void *H, int64_t H_batch_stride,
+                                      const int32_t *lengths, const void *queries, const void *out,
+                                      int32_t B, int32_t beam, int32_t n)
+{
+    if (!cfg || !valid_dtype(cfg->dtype) || !valid_dtype(cfg->out_dtype) || cfg->d_model < 1) return EL_ERR_INVALID_ARG;
+    if (mfma && !core_mfma_supported(cfg->dtype, cfg->d_model)) return EL_ERR_UNSUPPORTED;
+    el_status st = check_queries(*cfg, mfma != 0, queries, B, beam);
+    if (st != EL_OK) return st;
+    if ((st = check_out(*cfg, mfma != 0, out)) != EL_OK) return st;
+    return check_hidden(*cfg, mfma != 0, H, H_batch_stride, lengths, n);
+}
+
 int32_t el_attn_uses_mfma(const el_attn_ctx *ctx)
 {
     return (ctx && ctx->use_mfma_core && !(ctx->cfg.flags & EL_FLAG_FORCE_GENERIC)) ? 1 : 0;
@@ -337,8 +380,8 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
 {
     el_status st = check_step_args(ctx, queries, B, beam);
     if (st != EL_OK) return st;
-    if (!out) return EL_ERR_INVALID_ARG;
-    if ((st = check_keys(ctx, H, H_batch_stride, n)) != EL_OK) return st;
+    if ((st = check_out(ctx->cfg, el_attn_uses_mfma(ctx) != 0, out)) != EL_OK) return st;
+    if ((st = check_keys(ctx, H, H_batch_stride, lengths, n)) != EL_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
     const Workspace ws = carve(ctx);
@@ -356,7 +399,8 @@ el_status el_attn_decode_segment(el_attn_ctx *ctx, const void *H, int64_t H_batc
     el_status st = check_step_args(ctx, queries, B, beam);
     if (st != EL_OK) return st;
     if (!seg_A || !seg_lse) return EL_ERR_INVALID_ARG;
-    if ((st = check_keys(ctx, H, H_batch_stride, n)) != EL_OK) return st;
+    if (!aligned_to(seg_A, sizeof(float)) || !aligned_to(seg_lse, sizeof(float))) return EL_ERR_INVALID_ARG;
+    if ((st = check_keys(ctx, H, H_batch_stride, lengths, n)) != EL_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
     const Workspace ws = carve(ctx);
@@ -378,9 +422,10 @@ el_status el_attn_merge_segments(el_attn_ctx *ctx, int32_t nseg, const float *co
 {
     if (!ctx || !seg_A || !seg_lse || !out) return EL_ERR_INVALID_ARG;
     if (nseg < 1 || nseg > kMaxSegments) return EL_ERR_INVALID_ARG;
+    if (!aligned_to(out, (el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm) ? 16 : dtype_size(ctx->cfg.out_dtype))) return EL_ERR_INVALID_ARG;
     if (B < 1 || beam < 1 || B > ctx->cfg.max_batch || beam > ctx->cfg.max_beam) return EL_ERR_INVALID_ARG;
     for (int i = 0; i < nseg; ++i)
-        if (!seg_A[i] || !seg_lse[i]) return EL_ERR_INVALID_ARG;
+        if (!seg_A[i] || !seg_lse[i] || !aligned_to(seg_A[i], sizeof(float)) || !aligned_to(seg_lse[i], sizeof(float))) return EL_ERR_INVALID_ARG;
     if (!ctx->ws_base) return EL_ERR_WORKSPACE;
 
     hipStream_t s = (hipStream_t)stream;

@@ -21,7 +21,7 @@ DTYPE_CODES = {"f32": EL_F32, "f16": EL_F16, "bf16": EL_BF16}
 EXPORTED_SYMBOLS = (
     "el_attn_prepare", "el_attn_workspace_bytes", "el_attn_bind_workspace", "el_attn_decode_step",
     "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
-    "el_attn_uses_mfma", "el_attn_plan_preview",
+    "el_attn_uses_mfma", "el_attn_plan_preview", "el_attn_check_step_operands",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
     "el_attn_gather_batch", "el_attn_check_inputs",
     "el_attn_decode_segment", "el_attn_merge_segments", "el_attn_max_segments",
@@ -71,6 +71,8 @@ def _load():
     lib.el_attn_plan_preview.restype = ctypes.c_int
     lib.el_attn_uses_mfma.argtypes = [vp]
     lib.el_attn_uses_mfma.restype = i32
+    lib.el_attn_check_step_operands.argtypes = [ctypes.POINTER(ElAttnConfig), i32, vp, i64, vp, vp, vp, i32, i32, i32]
+    lib.el_attn_check_step_operands.restype = ctypes.c_int
     lib.el_attn_core_timing_enable.argtypes = [vp, i32]
     lib.el_attn_core_timing_enable.restype = ctypes.c_int
     lib.el_attn_core_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
@@ -153,6 +155,10 @@ def el_attn_plan_preview(B, beam, heads, d_model, n, compute_units):
 
 def el_attn_uses_mfma(ctx) -> int:
     return int(lib.el_attn_uses_mfma(ctx))
+
+
+def el_attn_check_step_operands(cfg: ElAttnConfig, mfma, H, H_batch_stride, lengths, queries, out, B, beam, n) -> int:
+    return int(lib.el_attn_check_step_operands(ctypes.byref(cfg), int(mfma), H, H_batch_stride, lengths, queries, out, B, beam, n))
 
 
 def el_attn_gather_batch(dtype, d_model, H_src, src_batch_stride, lengths_src, B_src,

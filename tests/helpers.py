@@ -30,6 +30,26 @@ def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(y - ref)) / np.max(np.abs(ref)))
 
 
+def err_report(y: np.ndarray, ref: np.ndarray) -> dict:
+    """The gated figure and the two others that are recorded next to it.
+    `tensor`: max|y - ref| / max|ref| over the whole tensor (the bar applies to this one);
+    `row`: the same ratio taken per output row (one (batch element, beam) pair), worst row;
+    `l2`: ||y - ref||_2 / ||ref||_2 over the whole tensor."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if not np.all(np.isfinite(y)):
+        return {"tensor": float("inf"), "row": float("inf"), "l2": float("inf")}
+    d = np.abs(y - ref).reshape(-1, y.shape[-1])
+    r = np.abs(ref).reshape(-1, y.shape[-1])
+    return {"tensor": float(d.max() / r.max()),
+            "row": float((d.max(axis=1) / r.max(axis=1)).max()),
+            "l2": float(np.sqrt((d * d).sum() / (r * r).sum()))}
+
+
+def fmt_report(rep: dict) -> str:
+    return f"err={rep['tensor']:.3e} worst_row={rep['row']:.3e} rel_l2={rep['l2']:.3e}"
+
+
 def oracle_out(w, W, H, Q, lens):
     import oracle
     Hc = np.where(np.isnan(H), 0.0, H) if np.isnan(H).any() else H   # oracle never reads them anyway

@@ -106,6 +106,36 @@ def test_gather_batch_rejects_bad_arguments_before_any_device_work(ea):
     assert call(sstride=64 * 1024 + 4) == I                                     # batch stride breaks the 16-byte alignment
 
 
+def test_step_operands_are_validated_on_the_host(ea):
+    """The checks decode_step applies to its operands, through the context-free entry point:
+    shapes, strides and, on the MFMA path, 16-byte alignment.  Fake pointers, never dereferenced."""
+    I, OK = ea.EL_ERR_INVALID_ARG, ea.EL_OK
+    H, Q, O, L = (ctypes.c_void_p(v) for v in (0x100000, 0x200000, 0x300000, 0x400000))
+    cfg = _cfg(ea, heads=16, d_model=1024, d_k=64, dtype=ea.EL_BF16, max_batch=8, max_beam=4, max_n=128)
+
+    def call(mfma=1, H=H, stride=128 * 1024, lengths=L, queries=Q, out=O, B=8, beam=4, n=128, cfg=cfg):
+        return ea.el_attn_check_step_operands(cfg, mfma, H, stride, lengths, queries, out, B, beam, n)
+
+    assert call() == OK and call(lengths=None) == OK and call(mfma=0) == OK
+    for bad in (dict(H=None), dict(queries=None), dict(out=None), dict(B=0), dict(B=9), dict(beam=5), dict(n=0), dict(n=129),
+                dict(stride=128 * 1024 - 8)):
+        assert call(**bad) == I, bad
+    off = lambda p, k: ctypes.c_void_p(p.value + k)
+    # MFMA path: 16-byte pieces
+    for bad in (dict(H=off(H, 2)), dict(H=off(H, 8)), dict(queries=off(Q, 2)), dict(out=off(O, 4)), dict(out=off(O, 8)),
+                dict(stride=128 * 1024 + 4), dict(stride=128 * 1024 + 1), dict(lengths=off(L, 2))):
+        assert call(**bad) == I, bad
+    assert call(stride=128 * 1024 + 8) == OK                     # 16 bytes more between batch elements
+    # generic path: element alignment only
+    assert call(mfma=0, H=off(H, 2), queries=off(Q, 2), stride=128 * 1024 + 1) == OK
+    assert call(mfma=0, H=off(H, 1)) == I and call(mfma=0, out=off(O, 2)) == I and call(mfma=0, lengths=off(L, 1)) == I
+    # a shape without MFMA kernels cannot be asked for their rules
+    c768 = _cfg(ea, heads=12, d_model=768, d_k=64, dtype=ea.EL_BF16, max_batch=8, max_beam=4, max_n=128)
+    assert call(cfg=c768, stride=128 * 768) == ea.EL_ERR_UNSUPPORTED
+    assert call(cfg=c768, mfma=0, stride=128 * 768) == OK
+    assert ea.lib.el_attn_check_step_operands(None, 1, H, 1, L, Q, O, 1, 1, 1) == I
+
+
 def test_plan_preview_on_the_benchmark_shapes(ea):
     """The automatic cut of the work, on a 256-unit device: host arithmetic only."""
     def plan(B, beam, heads, d_m, n):
