@@ -238,6 +238,28 @@ el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d
                                int32_t compute_units, int32_t *row_groups, int32_t *spans);
 
 /*
+ * el_attn_decode_step for callers that cannot allocate and have no workspace to bind: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, same
+ * result and same checks as el_attn_decode_step, but the intermediates of the step live in a fixed array
+ * of EL_ATTN_STATIC_SCRATCH_BYTES (32 MiB) that is part of the library's device code: every GPU the
+ * library is used on holds one copy until the process ends, and no workspace needs to be bound.  The
+ * call allocates nothing and only launches kernels.
+ *
+ * Limit: the intermediates of THIS call (about 41 bytes x B x R64 x d_model, R64 = heads * beam rounded
+ * up to a multiple of 64) must fit the array; otherwise WORKSPACE is returned and nothing is launched
+ * (at d_model = 1024, 16 heads, beam 4: B up to 12).  All calls on one GPU share that GPU's array,
+ * whatever their context or stream: calls that overlap in time on one GPU race.  Nothing in the array
+ * has to survive from call to call or start at zero.  The array's address on a device is resolved when
+ * a context is prepared on that device.
+ * Errors: as el_attn_decode_step; WORKSPACE as above; HIP if the array's address was not resolved.
+ */
+#define EL_ATTN_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+el_status el_attn_decode_step_static(el_attn_ctx *ctx,
+                                     const void *H, int64_t H_batch_stride, const int32_t *lengths,
+                                     const void *queries, void *out,
+                                     int32_t B, int32_t beam, int32_t n, void *stream);
+
+/*
  * The operand checks of el_attn_decode_step (shapes against the configured maxima, strides, and the
  * alignment rules stated there) as host arithmetic on a configuration alone: no context, no device, no
  * pointer is dereferenced.  `mfma` says which path's rules apply (what el_attn_uses_mfma would return

@@ -9,7 +9,31 @@
 
 using namespace el;
 
+// Scratch memory of el_attn_decode_step_static: every device the library's code object is loaded on holds its
+// own copy of this array until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels get the resolved per-device address as an ordinary pointer argument.
+constexpr size_t kStaticScratchBytes = EL_ATTN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];           // resolved address of `scratch` per device, null until resolved
+
+// Resolve the array's address on `device` (which must be the current device).  Called from el_attn_prepare,
+// so that the step itself finds it ready; returns null if the runtime cannot resolve it.
+void *resolve_static_scratch(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
+
+void *static_scratch_of(int device) { return (device >= 0 && device < kMaxDevices) ? g_scratch_ptr[device] : nullptr; }
 
 constexpr int32_t kVersion = 100; // 0.1.0
 
@@ -19,15 +43,14 @@ int round_up64(int v) { return (v + 63) / 64 * 64; }
 
 struct WsLayout {
     size_t off_Qp, off_ELQ, off_Xp, off_ML, off_Xn, off_A, off_E, total;
+    int slots;
 };
 
-WsLayout ws_layout(const el_attn_ctx *c, int B, int beam)
+// Workspace of a step with at most `batch` batch elements of at most `beam` beams.
+WsLayout ws_layout_for(const el_attn_ctx *c, int batch, int beam)
 {
-    // Offsets are computed for the prepared maxima so that a bound workspace is valid for
-    // every smaller call; B and beam are only used by callers that want exact sizes.
-    (void)B; (void)beam;
-    const size_t mb = (size_t)c->cfg.max_batch, mx = (size_t)c->cfg.max_beam;
-    const size_t d_m = (size_t)c->cfg.d_model, hd = (size_t)c->hd, Rp = (size_t)c->Rpad_max;
+    const size_t mb = (size_t)batch, mx = (size_t)beam;
+    const size_t d_m = (size_t)c->cfg.d_model, hd = (size_t)c->hd, Rp = (size_t)round_up64(c->cfg.heads * beam);
     WsLayout L;
     size_t o = 0;
     L.off_Qp = o;  o = align_up(o + mb * mx * hd * sizeof(float), 256);
@@ -38,13 +61,16 @@ WsLayout ws_layout(const el_attn_ctx *c, int B, int beam)
     L.off_A = o;   o = align_up(o + mb * mx * hd * sizeof(float), 256);
     L.off_E = o;   o = align_up(o + (mb + 1) * sizeof(int32_t), 256);
     L.total = o;
+    L.slots = batch * kMaxParts;
     return L;
 }
 
-Workspace carve(const el_attn_ctx *c)
+// Offsets of the bound workspace are those of the prepared maxima, so that it is valid for every smaller call.
+WsLayout ws_layout(const el_attn_ctx *c) { return ws_layout_for(c, c->cfg.max_batch, c->cfg.max_beam); }
+
+Workspace carve_from(void *ws_base, const WsLayout &L)
 {
-    const WsLayout L = ws_layout(c, 0, 0);
-    char *base = (char *)c->ws_base;
+    char *base = (char *)ws_base;
     Workspace w;
     w.Qp = (float *)(base + L.off_Qp);
     w.ELQ = (void *)(base + L.off_ELQ);
@@ -53,8 +79,11 @@ Workspace carve(const el_attn_ctx *c)
     w.Xn = (float *)(base + L.off_Xn);
     w.A = (float *)(base + L.off_A);
     w.E = (int32_t *)(base + L.off_E);
+    w.slots = L.slots;
     return w;
 }
+
+Workspace carve(const el_attn_ctx *c) { return carve_from(c->ws_base, ws_layout(c)); }
 
 void free_weights(el_attn_ctx *c)
 {
@@ -144,8 +173,7 @@ el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, 
 {
     constexpr float kLn2 = 0.6931471805599453f;
     if (el_attn_uses_mfma(ctx)) {
-        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus,
-                                           ctx->cfg.max_batch * kMaxParts);
+        const CorePlan pl = plan_core_mfma(p, ctx->splits_override, ctx->nrg_override, ctx->num_cus, ws.slots);
         fmt->pm = piece_map(pl, ws, p.B); fmt->Rstride = pl.Rs; fmt->ml_to_nat = kLn2;
         // a1 + a2: expanded queries in fp16, pre-multiplied by log2(e)/sqrt(d_k) so the core's softmax is an exp2
         const float qscale = 1.4426950408889634f / sqrtf((float)p.d_k);
@@ -245,7 +273,7 @@ el_status el_attn_prepare(const el_attn_config *cfg,
     c->cfg = *cfg;
     c->hd = cfg->heads * cfg->d_k;
     c->Rpad_max = round_up64(cfg->heads * cfg->max_beam);
-    c->ws_need = ws_layout(c, 0, 0).total;
+    c->ws_need = ws_layout(c).total;
     c->use_mfma_core = core_mfma_supported(cfg->dtype, cfg->d_model) ? 1 : 0;
 
     hipStream_t s = (hipStream_t)stream;
@@ -253,6 +281,7 @@ el_status el_attn_prepare(const el_attn_config *cfg,
     if (hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->num_cus < 1) {
         delete c; return EL_ERR_HIP;
     }
+    if (!resolve_static_scratch(c->device)) { delete c; return EL_ERR_HIP; }      // for el_attn_decode_step_static
 
     const size_t es = dtype_size(cfg->dtype);
     const size_t wbytes = (size_t)cfg->d_model * c->hd * es;
@@ -385,6 +414,28 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
 
     hipStream_t s = (hipStream_t)stream;
     const Workspace ws = carve(ctx);
+    const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
+    StepFormats fmt;
+    if ((st = run_a1_to_a6(ctx, p, ws, s, &fmt)) != EL_OK) return st;
+    return run_a7(ctx, p, ws, ctx->w.c_out, s);
+}
+
+el_status el_attn_decode_step_static(el_attn_ctx *ctx, const void *H, int64_t H_batch_stride,
+                                     const int32_t *lengths, const void *queries, void *out,
+                                     int32_t B, int32_t beam, int32_t n, void *stream)
+{
+    el_status st = check_step_args(ctx, queries, B, beam);
+    if (st != EL_OK) return st;
+    if ((st = check_out(ctx->cfg, el_attn_uses_mfma(ctx) != 0, out)) != EL_OK) return st;
+    if ((st = check_hidden(ctx->cfg, el_attn_uses_mfma(ctx) != 0, H, H_batch_stride, lengths, n)) != EL_OK) return st;
+    // the workspace of THIS call's batch and beam count must fit the static array
+    const WsLayout L = ws_layout_for(ctx, B, beam);
+    if (L.total > kStaticScratchBytes) return EL_ERR_WORKSPACE;
+    void *base = static_scratch_of(ctx->device);
+    if (!base) return EL_ERR_HIP;
+
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace ws = carve_from(base, L);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
     StepFormats fmt;
     if ((st = run_a1_to_a6(ctx, p, ws, s, &fmt)) != EL_OK) return st;

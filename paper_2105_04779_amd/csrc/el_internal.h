@@ -136,6 +136,7 @@ struct Workspace {
     float *Xn;      // [B, R, d_m]                  merged, normalised weighted sums (generic path)
     float *A;       // [B*beam, hd]                 a6 result: fp32 (generic) or fp16 (MFMA GEMMs)
     int32_t *E;     // [B+1]                        prefix sum of tile counts (flattened cut of the MFMA core)
+    int slots;      // pieces Xp and ML have room for (batch elements the workspace was laid out for x kMaxParts)
 };
 
 struct Weights {    // library-owned copies in the storage dtype

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = (
     "el_attn_prepare", "el_attn_workspace_bytes", "el_attn_bind_workspace", "el_attn_decode_step",
     "el_attn_expand_query", "el_attn_set_splits", "el_attn_max_splits", "el_attn_set_row_groups",
     "el_attn_uses_mfma", "el_attn_plan_preview", "el_attn_check_step_operands",
+    "el_attn_decode_step_static",
     "el_attn_core_timing_enable", "el_attn_core_timing_read",
     "el_attn_gather_batch", "el_attn_check_inputs",
     "el_attn_decode_segment", "el_attn_merge_segments", "el_attn_max_segments",
@@ -59,6 +60,8 @@ def _load():
     lib.el_attn_bind_workspace.restype = ctypes.c_int
     lib.el_attn_decode_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, vp]
     lib.el_attn_decode_step.restype = ctypes.c_int
+    lib.el_attn_decode_step_static.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, i32, vp]
+    lib.el_attn_decode_step_static.restype = ctypes.c_int
     lib.el_attn_expand_query.argtypes = [vp, vp, vp, i32, i32, vp]
     lib.el_attn_expand_query.restype = ctypes.c_int
     lib.el_attn_set_splits.argtypes = [vp, i32]
@@ -132,6 +135,10 @@ def el_attn_bind_workspace(ctx, dev_ptr, nbytes) -> int:
 
 def el_attn_decode_step(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream=None) -> int:
     return lib.el_attn_decode_step(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream)
+
+
+def el_attn_decode_step_static(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream=None) -> int:
+    return int(lib.el_attn_decode_step_static(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n, stream))
 
 
 def el_attn_expand_query(ctx, queries, elq_out, B, beam, stream=None) -> int:
