@@ -24,6 +24,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ROTATE_BYTES = 768e6           # >= 3x the 256 MB memory-side cache
 
+ARITH = {
+    "bf16": "bf16 MFMA in the attention core (EL-Q and P as high+low bf16 pairs), fp16 MFMA in the projections, fp32 accumulation and softmax",
+    "f16": "fp16 MFMA (EL-Q as a high+low fp16 pair), fp32 accumulation and softmax",
+    "f32": "fp32 vector FMA",
+}
+
+
+def kernel_source_digest() -> str:
+    """sha256 over the library's kernel sources (names and contents, sorted): says which kernels a stored counter
+    figure was taken on, without needing the repository's history on the machine that runs the benchmark."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2105_04779_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -203,8 +222,7 @@ def measure(a, w, torch, np, el_attn, tm, wl):
     td = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[w.dtype]
 
     # ---- inputs, resident in HBM before anything is timed -----------------------------------
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import device_weights
+    device_weights = el_attn.device_weights
     # `--layers L`: L attention layers with their own weights read the same H in every step (what the L
     # decoder layers of one model do with one encoder output); layer 0 has the workload's own weights
     layers = []
@@ -262,13 +280,19 @@ def measure(a, w, torch, np, el_attn, tm, wl):
     step_bytes = tm.step_algorithmic_bytes(sum_len, w.B, w.beam, w.d_m, w.heads * w.d_k, w.elem_bytes, 4)
     achieved = core_bytes / (core_avg_ms * 1e-3) / 1e9
     # HBM bytes per launch of that kernel from the committed rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE,
-    # each scaled by what the same counter reads for a plain copy of known size); null if none is committed
+    # each scaled by what the same counter reads for a plain copy of known size).  The counters cannot be read
+    # inside this run, so the stored figure carries the digest of the kernel sources it was taken on: it is
+    # reported only while those sources are unchanged, and is null otherwise (or if none is committed).
     traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
     if os.path.exists(tpath) and a.layers == 1:
         with open(tpath) as f:
             traffic_detail = json.load(f)
-        traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
+        if traffic_detail.get("kernel_source_sha256") == kernel_source_digest():
+            traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
+        else:
+            traffic_detail = {"stale": True, "reason": "the kernel sources changed since the committed counter run",
+                              "counters_taken_on": traffic_detail.get("kernel_source_sha256")}
 
     L = a.layers
     line = {
@@ -278,7 +302,7 @@ def measure(a, w, torch, np, el_attn, tm, wl):
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": w.dtype, "arith": ARITH[w.dtype] if layer.uses_mfma else ARITH["f32"], "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "beam": w.beam, "heads": w.heads, "d_m": w.d_m, "d_k": w.d_k,
                    "n": w.n, "sum_len": sum_len, "h_buffers_rotated": nbuf, "mfma_path": layer.uses_mfma,
                    "splits": a.splits, "layers": L},

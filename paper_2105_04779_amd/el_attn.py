@@ -227,6 +227,23 @@ def _stream_handle():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def to_device(x32, dtype: str, device="cuda"):
+    """float32 values already rounded to `dtype` ("f32", "f16", "bf16") -> device tensor of that dtype, bit-exact
+    (argument marshalling for numpy-side callers; bf16 has no numpy type, so its bit pattern travels as int16)."""
+    import numpy as np
+    import torch
+    from . import workloads as wl
+    bits = wl.storage_bits(x32, dtype)
+    if dtype == "bf16":
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(bits).to(device)
+
+
+def device_weights(W: dict, dtype: str):
+    """The weight dictionary of `workloads.weights` (numpy float32, rounded to `dtype`) on the device."""
+    return {k: (None if v is None else to_device(v, dtype)) for k, v in W.items()}
+
+
 def gather_batch(H_src, lengths_src, index, *, H_dst=None, lengths_dst=None):
     """H_dst[i, :len] = H_src[index[i], :len], lengths_dst[i] = len (marshalling only; see el_attn_gather_batch).
 

@@ -4,21 +4,9 @@ from __future__ import annotations
 import numpy as np
 
 from paper_2105_04779_amd import workloads as wl
+from paper_2105_04779_amd.el_attn import device_weights, to_device  # noqa: F401  (re-exported for the tests)
 
 TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
-
-
-def to_device(x32: np.ndarray, dtype: str, device="cuda"):
-    """float32 values already rounded to `dtype` -> device tensor of that dtype (bit-exact)."""
-    import torch
-    bits = wl.storage_bits(x32, dtype)
-    if dtype == "bf16":
-        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
-    return torch.from_numpy(bits).to(device)
-
-
-def device_weights(W: dict, dtype: str):
-    return {k: (None if v is None else to_device(v, dtype)) for k, v in W.items()}
 
 
 def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
