@@ -107,6 +107,11 @@ int auto_parts_generic(const Problem &p)
     return parts < 1 ? 1 : parts;
 }
 
+// The launchers report a failed launch through hipGetLastError(), which returns the last error ANY runtime call
+// of this thread left behind, other libraries' included (a device probe that failed before the runtime was up,
+// say).  Every entry point that launches starts from a clean slate.
+void forget_foreign_errors() { (void)hipGetLastError(); }
+
 bool aligned_to(const void *p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Element alignment for every path; on the MFMA path operands are fetched and stored in 16-byte pieces.
@@ -277,6 +282,7 @@ el_status el_attn_prepare(const el_attn_config *cfg,
     c->use_mfma_core = core_mfma_supported(cfg->dtype, cfg->d_model) ? 1 : 0;
 
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return EL_ERR_HIP; }
     if (hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->num_cus < 1) {
         delete c; return EL_ERR_HIP;
@@ -396,6 +402,7 @@ el_status el_attn_expand_query(el_attn_ctx *ctx, const void *queries, float *elq
     if (!elq_out) return EL_ERR_INVALID_ARG;
     if (!ctx->ws_base) return EL_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, nullptr, 0, nullptr, queries, nullptr, B, beam, 1);
     if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
@@ -413,6 +420,7 @@ el_status el_attn_decode_step(el_attn_ctx *ctx, const void *H, int64_t H_batch_s
     if ((st = check_keys(ctx, H, H_batch_stride, lengths, n)) != EL_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
     StepFormats fmt;
@@ -435,6 +443,7 @@ el_status el_attn_decode_step_static(el_attn_ctx *ctx, const void *H, int64_t H_
     if (!base) return EL_ERR_HIP;
 
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     const Workspace ws = carve_from(base, L);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, out, B, beam, n);
     StepFormats fmt;
@@ -454,6 +463,7 @@ el_status el_attn_decode_segment(el_attn_ctx *ctx, const void *H, int64_t H_batc
     if ((st = check_keys(ctx, H, H_batch_stride, lengths, n)) != EL_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, H, H_batch_stride, lengths, queries, nullptr, B, beam, n);
     StepFormats fmt;
@@ -480,6 +490,7 @@ el_status el_attn_merge_segments(el_attn_ctx *ctx, int32_t nseg, const float *co
     if (!ctx->ws_base) return EL_ERR_WORKSPACE;
 
     hipStream_t s = (hipStream_t)stream;
+    forget_foreign_errors();
     const Workspace ws = carve(ctx);
     const Problem p = make_problem(ctx, nullptr, 0, nullptr, nullptr, out, B, beam, 1);
     const bool f16_path = el_attn_uses_mfma(ctx) && ctx->use_mfma_gemm;

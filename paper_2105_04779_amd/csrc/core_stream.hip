@@ -495,21 +495,26 @@ k_core_stream(const StreamArgs a)
 #pragma unroll
                     for (int k = 0; k < 16; ++k) X[mb][k] *= al;
             }
-            u4 hprev = u4{0u, 0u, 0u, 0u};
+            // An LDS read holds its wavefront for about as long as one of these MFMAs runs, so they alternate: the
+            // MFMAs of block mb (both planes, the second accumulating on the first), each followed by one of the
+            // two reads that refill the fragment of block mb - 1, whose MFMAs have been issued by then.
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; mb <= MB; ++mb) {
                 __builtin_amdgcn_sched_barrier(0);
-                // plane 0 of this block, then plane 1 of the block before it: no MFMA waits for its predecessor
-                const s4 lo = tb[SET][mb][0], hi = tb[SET][mb][1];
-                const u4 hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
-                X[mb] = Mma<BF16>::s32(hfrag, P[0], X[mb]);
-                if (NP == 2 && mb > 0) X[mb - 1] = Mma<BF16>::s32(hprev, P[NP - 1], X[mb - 1]);
-                hprev = hfrag;
-                tb[SET][mb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[mb & 3] + (mb >> 2) * 256));
-                tb[SET][mb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[mb & 3] + (mb >> 2) * 256));
-                if (mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
+                u4 hfrag = u4{0u, 0u, 0u, 0u};
+                if (mb < MB) {
+                    const s4 lo = tb[SET][mb][0], hi = tb[SET][mb][1];
+                    hfrag = __builtin_bit_cast(u4, s8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+                    X[mb] = Mma<BF16>::s32(hfrag, P[0], X[mb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (mb > 0) tb[SET][mb - 1][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_lo[(mb - 1) & 3] + ((mb - 1) >> 2) * 256));
+                __builtin_amdgcn_sched_barrier(0);
+                if (mb < MB && NP == 2) X[mb] = Mma<BF16>::s32(hfrag, P[NP - 1], X[mb]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (mb > 0) tb[SET][mb - 1][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[(mb - 1) & 3] + ((mb - 1) >> 2) * 256));
+                if (mb < MB && mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
             }
-            if (NP == 2) X[MB - 1] = Mma<BF16>::s32(hprev, P[NP - 1], X[MB - 1]);
             fetch_advance();
             __builtin_amdgcn_sched_barrier(0);
         };

@@ -127,6 +127,7 @@ extern "C" el_status el_attn_gather_batch(el_dtype dtype, int32_t d_model,
     if ((src_batch_stride * es) % 16 != 0 || (dst_batch_stride * es) % 16 != 0) return EL_ERR_INVALID_ARG;
     if (B_dst > 65535) return EL_ERR_INVALID_ARG;      // grid.y
     const dim3 grid((n + el::kRowsPerBlock - 1) / el::kRowsPerBlock, B_dst), block(256);
+    (void)hipGetLastError();      // errors other libraries left behind in this thread are not this launch's
     hipLaunchKernelGGL(el::k_gather_batch, grid, block, 0, (hipStream_t)stream,
                        (const char *)H_src, src_batch_stride * es, lengths_src, B_src,
                        (char *)H_dst, dst_batch_stride * es, lengths_dst, index, n, (int)row_bytes);
@@ -147,6 +148,7 @@ extern "C" el_status el_attn_check_inputs(el_dtype dtype, int32_t d_model,
     if (((uintptr_t)H & 15) || ((uintptr_t)report & 7) || (H_batch_stride * es) % 16 != 0) return EL_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     unsigned long long *rep = (unsigned long long *)report;
+    (void)hipGetLastError();      // errors other libraries left behind in this thread are not this launch's
     hipLaunchKernelGGL(el::k_zero_report, dim3(1), dim3(64), 0, s, rep);
     const dim3 grid((n + el::kRowsPerCheckBlock - 1) / el::kRowsPerCheckBlock, B), block(256);
     const char *Hc = (const char *)H;

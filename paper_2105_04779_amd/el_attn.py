@@ -50,6 +50,13 @@ def _load():
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2105_04779_amd.build` "
             "(or __graft_entry__.build()); there is no fallback path.")
+    # PyTorch ships a HIP runtime of its own.  The tensors this binding is handed live in that runtime, so it has to
+    # be in the process before the library is loaded: loaded the other way round, the library binds to the system's
+    # copy and the two runtimes then disagree about the device ("no ROCm-capable device", crashes).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     lib.el_attn_prepare.argtypes = [ctypes.POINTER(ElAttnConfig)] + [vp] * 8 + [vp, ctypes.POINTER(vp)]
