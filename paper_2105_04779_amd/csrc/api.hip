@@ -205,7 +205,7 @@ el_status run_a1_to_a6(el_attn_ctx *ctx, const Problem &p, const Workspace &ws, 
         if (launch_qproj_generic(ctx, p, ws, s) != hipSuccess) return EL_ERR_HIP;
         if (launch_elq_generic(ctx, p, ws.Qp, (float *)ws.ELQ, s) != hipSuccess) return EL_ERR_HIP;
         const int parts = ctx->splits_override ? ctx->splits_override : auto_parts_generic(p);
-        fmt->pm.E = nullptr; fmt->pm.parts = parts; fmt->pm.G = 0; fmt->pm.lfloor = 0; fmt->pm.B = p.B;
+        fmt->pm.E = nullptr; fmt->pm.parts = parts; fmt->pm.G = 0; fmt->pm.lfloor = 0; fmt->pm.B = p.B; fmt->pm.kcost = 0;
         fmt->Rstride = p.R; fmt->ml_to_nat = 1.f;
         const bool timed = ctx->ev && ctx->ev_used < ctx->ev_cap;
         if (timed && hipEventRecord(ctx->ev[2 * ctx->ev_used], s) != hipSuccess) return EL_ERR_HIP;

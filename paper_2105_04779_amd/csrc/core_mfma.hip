@@ -69,6 +69,11 @@ bool core_mfma_supported(int dtype, int d_m)
 // length keeps every element within kMaxParts pieces.  Batches beyond kScanMax elements are not cut as
 // one list: one workgroup per (element, row block), scheduled by the hardware.
 constexpr int kMinSpan = 8;
+// What moving on to the next batch element costs a workgroup, in tiles of streaming time: the expanded queries of
+// the new element (128 KB for 32 rows) and the write-out of the finished piece.  Spans that cross an element hold
+// that many tiles fewer, so that all workgroups finish together (measured on 64 ragged inputs of 512-1024 rows:
+// workgroups with a crossing ended 5-6 us after the others).
+constexpr int kBoundaryCost = 4;
 
 CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override, int num_cus, int max_slots)
 {
@@ -80,7 +85,7 @@ CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override,
     const int tiles = (p.n + 15) / 16;
     pl.flat = p.B <= kScanMax && max_slots - p.B >= 1 ? 1 : 0;
     if (!pl.flat) {
-        pl.G = p.B; pl.lfloor = tiles; pl.parts = 1; pl.slots = p.B;
+        pl.G = p.B; pl.lfloor = tiles; pl.kcost = 0; pl.parts = 1; pl.slots = p.B;
         return pl;
     }
     long G;
@@ -95,6 +100,7 @@ CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override,
     if (G < 1) G = 1;
     pl.G = (int)G;
     pl.lfloor = (tiles + kMaxParts - 2) / (kMaxParts - 1);
+    pl.kcost = kBoundaryCost;
     pl.parts = kMaxParts;
     pl.slots = pl.G + p.B;
     return pl;
@@ -104,7 +110,7 @@ PieceMap piece_map(const CorePlan &pl, const Workspace &ws, int B)
 {
     PieceMap m;
     m.E = pl.flat ? ws.E : nullptr;
-    m.parts = 1; m.G = pl.G; m.lfloor = pl.lfloor; m.B = B;
+    m.parts = 1; m.G = pl.G; m.lfloor = pl.lfloor; m.B = B; m.kcost = pl.kcost;
     return m;
 }
 
@@ -130,7 +136,7 @@ hipError_t launch_core_mfma(const el_attn_ctx *, const Problem &p, const Workspa
     a.elq = (const uint16_t *)ws.ELQ;
     a.Xp = (f16_t *)ws.Xp; a.ML = ws.ML; a.E = pl.flat ? ws.E : nullptr;
     a.n = p.n; a.B = p.B; a.R = p.R; a.Rs = pl.Rs; a.nblocks = pl.nblocks;
-    a.flat = pl.flat; a.G = pl.G; a.lfloor = pl.lfloor;
+    a.flat = pl.flat; a.G = pl.G; a.lfloor = pl.lfloor; a.kcost = pl.kcost;
     // H is read once per step; when a batch of it is larger than the 256 MB memory-side cache, keeping its lines
     // out of the caches leaves them to the data that is re-read and raises the streaming rate (measured, core
     // kernel: 1 GB of per-beam histories 216 -> 184 us; 640 MB shared by two row blocks 149 -> 144 us).  Below

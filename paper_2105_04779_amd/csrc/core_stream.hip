@@ -131,7 +131,7 @@ k_core_stream(const StreamArgs a)
     const int per_xcd = (nwg + 7) >> 3;
     const int place = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (place >= nwg) return;
-    const int span = place / a.nblocks, rb = place % a.nblocks;
+    const int span = place / a.nblocks, rb = place % a.nblocks;   // (the piece slots are span + element: see PieceMap)
     const int row0 = rb * ROWS;                      // first expanded-query row of this workgroup
 
     auto clamp_len = [&](int v) { return min(max(v, 1), a.n); };
@@ -139,39 +139,52 @@ k_core_stream(const StreamArgs a)
     // ---- where this span starts: element b0, tile kt0 of it, nspan tiles in all ----
     int b0, kt0, nspan, len0;
     if (a.flat) {
+        // Tiles on the cost axis (see PieceMap): element b starts at E[b] + kcost * b with a gap of kcost units, then
+        // its tiles.  This span is [c0, c1) of that axis.
         for (int i = tid; i < a.B; i += 512) Lt[i] = clamp_len(a.lengths ? a.lengths[i] : a.n);
         __syncthreads();
         int part = 0;
         for (int i = l; i < a.B; i += 64) part += (Lt[i] + kTile - 1) / kTile;
         const int total = wave_sum(part);
-        const int lspan = max((total + a.G - 1) / a.G, a.lfloor);
-        const int s0 = span * lspan;
-        nspan = min(lspan, total - s0);
+        const int cspan = flat_cspan(total, a.B, a.G, a.lfloor, a.kcost);
+        const int c0 = span * cspan, c1 = min(c0 + cspan, total + a.kcost * a.B);
         const bool writer = place == 0 && w == 0 && a.E != nullptr;       // one wavefront publishes the prefix for a6
         if (writer && l == 0) a.E[0] = 0;
+        // tiles_before(c): tiles at coordinates below c; for c0 also the element and tile the span starts at
         b0 = -1; kt0 = 0;
-        int run = 0;
+        int t_lo = 0, t_hi = -1, run = 0;                                 // run: tiles of the chunks already scanned
         for (int c = 0; c * 64 < a.B; ++c) {
             const int i = c * 64 + l;
-            int inc = i < a.B ? (Lt[i] + kTile - 1) / kTile : 0;
+            const int mine = i < a.B ? (Lt[i] + kTile - 1) / kTile : 0;
+            int inc = mine;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const int up = __shfl_up(inc, o, 64);
                 if (l >= o) inc += up;
             }
-            inc += run;
+            inc += run;                                                   // tiles of elements 0..i
             if (writer && i < a.B) a.E[i + 1] = inc;
-            const int cnt = __builtin_popcountll(__ballot(i < a.B && inc <= s0));
-            if (b0 < 0 && cnt < 64 && c * 64 + cnt < a.B) {
-                b0 = c * 64 + cnt;
-                kt0 = s0 - (cnt ? __shfl(inc, cnt - 1, 64) : run);
-                if (!writer) break;
+            const int cend = inc + a.kcost * (i + 1);                    // one past the last coordinate of element i
+            // the first element that ends beyond c0 holds the span's first tile (or the gap before its tiles)
+            const int n0 = __builtin_popcountll(__ballot(i < a.B && cend <= c0));
+            if (b0 < 0 && n0 < 64 && c * 64 + n0 < a.B) {
+                b0 = c * 64 + n0;
+                const int tiles_b = __shfl(mine, n0, 64), end_b = __shfl(cend, n0, 64);
+                kt0 = max(c0 - (end_b - tiles_b), 0);                     // coordinate of its tile 0 is end_b - tiles_b
+                t_lo = __shfl(inc, n0, 64) - tiles_b + kt0;
+            }
+            const int n1 = __builtin_popcountll(__ballot(i < a.B && cend <= c1));
+            if (t_hi < 0 && n1 < 64 && c * 64 + n1 < a.B) {
+                const int tiles_b = __shfl(mine, n1, 64), end_b = __shfl(cend, n1, 64);
+                t_hi = __shfl(inc, n1, 64) - tiles_b + max(c1 - (end_b - tiles_b), 0);
             }
             run = __shfl(inc, 63, 64);
         }
+        if (t_hi < 0) t_hi = total;                                      // c1 is the end of the axis
         b0 = __builtin_amdgcn_readfirstlane(b0);
         kt0 = __builtin_amdgcn_readfirstlane(kt0);
-        if (nspan <= 0 || b0 < 0) return;            // the list is shorter than G spans of the floor length
+        nspan = __builtin_amdgcn_readfirstlane(t_hi - t_lo);
+        if (nspan <= 0 || b0 < 0) return;            // the axis is shorter than G spans of the floor length, or the span is all gap
         len0 = __builtin_amdgcn_readfirstlane(Lt[b0]);
     } else {
         b0 = span; kt0 = 0;

@@ -97,22 +97,30 @@ constexpr int kScanMax = 1024;      // most batch elements whose tiles the strea
 // Where the partial results ("pieces") of batch element b live: `np` consecutive slots from `slot0` in the
 // partial buffers Xp [slot, Rs, d_m] and ML [slot, Rs, 2].
 //   fixed cut      every element is cut into `parts` key ranges: slots b*parts .. b*parts+parts-1;
-//   flattened cut  the 16-row tiles of all elements form one list, cut into G spans of
-//                  lspan = max(ceil(total / G), lfloor) tiles; the piece of (span g, element b) is slot g + b
-//                  (unique: along the list, span and element never decrease and one of them grows from piece
-//                  to piece).  E [B+1] is the prefix sum of the elements' tile counts, written by the core.
+//   flattened cut  the 16-row tiles of all elements lie on one axis, element after element, each element preceded
+//                  by a gap of `kcost` units (what moving on to a new element costs a workgroup, in tiles): tile kt
+//                  of element b sits at coordinate E[b] + kcost * (b + 1) + kt, where E [B+1] is the prefix sum of
+//                  the elements' tile counts, written by the core.  The axis is cut into G spans of
+//                  cspan = max(ceil(length / G), lfloor + kcost) units, so a span that crosses into a new element
+//                  holds kcost tiles fewer; the piece of (span g, element b) is slot g + b (unique: along the
+//                  axis, span and element never decrease and one of them grows from piece to piece).
 struct PieceMap {
     const int32_t *E;       // null: fixed cut
     int parts;              // fixed cut: parts per element
-    int G, lfloor, B;       // flattened cut
+    int G, lfloor, B, kcost; // flattened cut
 };
+__host__ __device__ __forceinline__ int flat_cspan(int total_tiles, int B, int G, int lfloor, int kcost)
+{
+    const int length = total_tiles + kcost * B;
+    const int c = (length + G - 1) / G;
+    return c > lfloor + kcost ? c : lfloor + kcost;
+}
 __device__ __forceinline__ void piece_range(const PieceMap &m, int b, int &slot0, int &np)
 {
     if (!m.E) { slot0 = b * m.parts; np = m.parts; return; }
-    const int total = m.E[m.B];
-    int lspan = (total + m.G - 1) / m.G;
-    lspan = lspan > m.lfloor ? lspan : m.lfloor;
-    const int g_lo = m.E[b] / lspan, g_hi = (m.E[b + 1] - 1) / lspan;
+    const int cspan = flat_cspan(m.E[m.B], m.B, m.G, m.lfloor, m.kcost);
+    const int first = m.E[b] + m.kcost * (b + 1), last = m.E[b + 1] + m.kcost * (b + 1) - 1;
+    const int g_lo = first / cspan, g_hi = last / cspan;
     slot0 = g_lo + b; np = g_hi - g_lo + 1;
 }
 
@@ -209,6 +217,7 @@ struct CorePlan {
     int flat;     // 1: the tiles of all elements are cut as one list into G spans; 0: one workgroup per (element, row block)
     int G;        // spans (flat) or batch elements (not flat)
     int lfloor;   // flat: floor on the span length in tiles, so that no element has more than kMaxParts pieces
+    int kcost;    // flat: what crossing into a new element costs a workgroup, in tiles (see PieceMap)
     int parts;    // most pieces per (batch element, row)
     int slots;    // piece slots the partial buffers must hold
 };
@@ -223,7 +232,7 @@ struct StreamArgs {
     float *ML;               // [slot, Rs, 2]  (reference max in log2 units, sum)
     int32_t *E;              // [B+1] prefix sum of tile counts (flat cut), written by the kernel; may be null
     int n, B, R, Rs, nblocks;
-    int flat, G, lfloor;
+    int flat, G, lfloor, kcost;
     int stream_hint;         // nonzero: fetch H with the non-temporal hint (H far larger than the memory-side cache)
 };
 hipError_t launch_core_stream(const StreamArgs &a, int d_m, bool bf16, int rg, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
