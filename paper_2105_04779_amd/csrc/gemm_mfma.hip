@@ -46,6 +46,7 @@ struct GemmArgs {
     const float *ML;
     PieceMap pm;
     int parts, Rs;
+    int N_heads;          // k_vproj_slab: heads (the grid is one-dimensional, see the kernel)
 };
 
 template <bool BF> struct Frag;
@@ -178,7 +179,17 @@ k_vproj_slab(const GemmArgs g)
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = l & 15, q4 = l >> 4;
-    const int m0 = blockIdx.x * 16, head = blockIdx.y;
+    // Workgroup ids that differ by a multiple of 8 share an XCD and its L2.  Heads are dealt out so that an XCD
+    // works on as few of them as possible (heads / 8 when that divides): it then pulls only those heads' weights
+    // from memory, once, instead of every XCD pulling all of W^V.
+    int m0, head;
+    {
+        const int heads = g.N_heads, xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int hp = (heads + 7) >> 3;                 // heads per XCD
+        head = xcd * hp + j % hp;
+        m0 = (j / hp) * 16;
+        if (head >= heads || m0 >= g.M) return;
+    }
     const unsigned s_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)S;
 
     // ---- weights of this head: rows 16w..16w+15 of its 64, straight into LDS ----
@@ -466,7 +477,9 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     g.A = ws.Xp; g.Bt = ctx->w.WvT; g.C = ws.A; g.ML = ws.ML; g.parts = pl.parts; g.Rs = pl.Rs;
     g.pm = piece_map(pl, ws, p.B);
     g.N = p.d_k; g.K = p.d_m; g.lda = p.d_m; g.ldb = p.d_m; g.ldc = p.hd;
-    const dim3 grid((g.M + 15) / 16, p.heads), block(256);
+    g.N_heads = p.heads;
+    const int hp = (p.heads + 7) / 8;                    // heads per XCD; 8 * hp * (row tiles) workgroups
+    const dim3 grid(8 * hp * ((g.M + 15) / 16)), block(256);
     if (p.d_m == 1024) hipLaunchKernelGGL((k_vproj_slab<1024>), grid, block, 0, s, g);
     else hipLaunchKernelGGL((k_vproj_slab<512>), grid, block, 0, s, g);
     return hipGetLastError();
