@@ -115,13 +115,29 @@ __host__ __device__ __forceinline__ int flat_cspan(int total_tiles, int B, int G
     const int c = (length + G - 1) / G;
     return c > lfloor + kcost ? c : lfloor + kcost;
 }
+// What every look-up of one launch shares: the span length on the cost axis (a division, done once).
+struct PieceCut { int cspan; };
+__device__ __forceinline__ PieceCut piece_cut(const PieceMap &m, int E_total)       // E_total = E[B]
+{
+    return PieceCut{m.E ? flat_cspan(E_total, m.B, m.G, m.lfloor, m.kcost) : 1};
+}
+__device__ __forceinline__ PieceCut piece_cut(const PieceMap &m) { return piece_cut(m, m.E ? m.E[m.B] : 0); }
+// (E_b, E_b1) = (E[b], E[b+1]), for callers that fetch them ahead of time
+__device__ __forceinline__ void piece_range(const PieceMap &m, const PieceCut &c, int b, int E_b, int E_b1, int &slot0, int &np)
+{
+    if (!m.E) { slot0 = b * m.parts; np = m.parts; return; }
+    const int first = E_b + m.kcost * (b + 1), last = E_b1 + m.kcost * (b + 1) - 1;
+    const int g_lo = first / c.cspan;
+    // an element has at most kMaxParts pieces: the last span is found by stepping, not by a second division
+    int cnt = 1;
+    for (int k = 1; k < kMaxParts; ++k) cnt += last >= (g_lo + k) * c.cspan ? 1 : 0;
+    if (last >= (g_lo + kMaxParts) * c.cspan) cnt = last / c.cspan - g_lo + 1;     // never with a plan that respects kMaxParts
+    slot0 = g_lo + b; np = cnt;
+}
 __device__ __forceinline__ void piece_range(const PieceMap &m, int b, int &slot0, int &np)
 {
     if (!m.E) { slot0 = b * m.parts; np = m.parts; return; }
-    const int cspan = flat_cspan(m.E[m.B], m.B, m.G, m.lfloor, m.kcost);
-    const int first = m.E[b] + m.kcost * (b + 1), last = m.E[b + 1] + m.kcost * (b + 1) - 1;
-    const int g_lo = first / cspan, g_hi = last / cspan;
-    slot0 = g_lo + b; np = g_hi - g_lo + 1;
+    piece_range(m, piece_cut(m), b, m.E[b], m.E[b + 1], slot0, np);
 }
 
 // ---- problem description handed to the launchers ------------------------------------------

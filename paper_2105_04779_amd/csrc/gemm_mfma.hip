@@ -192,15 +192,32 @@ k_vproj_slab(const GemmArgs g)
     }
     const unsigned s_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)S;
 
-    // ---- weights of this head: rows 16w..16w+15 of its 64, straight into LDS ----
+    // Order of the requests: the piece table first (a few scalars; the answer arrives while the first half of
+    // the weights is being requested), then half of the weights, then the statistics and the partial rows
+    // (which still have arithmetic ahead of them), then the rest of the weights (which go straight to LDS).
+    int e_tot = 0, e_lo[4], e_hi[4], b_of[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int rr = 16 * w + i;
-        const char *sbase = (const char *)g.Bt + (size_t)(head * 64 + rr) * g.ldb * 2;
-        const unsigned voff = (unsigned)((l ^ row_swizzle(i)) << 4);
-        if (ROWB == 2048) dma_row_2k(s_lds + A_BYTES + rr * ROWB, voff, sbase);
-        else dma_piece(s_lds + A_BYTES + rr * ROWB, voff, sbase);
+    for (int ii = 0; ii < 4; ++ii) {
+        b_of[ii] = __builtin_amdgcn_readfirstlane(min(m0 + 4 * w + ii, g.M - 1) / g.x);
+        e_lo[ii] = e_hi[ii] = 0;
     }
+    if (g.pm.E) {
+        e_tot = g.pm.E[g.pm.B];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) { e_lo[ii] = g.pm.E[b_of[ii]]; e_hi[ii] = g.pm.E[b_of[ii] + 1]; }
+    }
+    // ---- weights of this head: rows 16w..16w+15 of its 64, straight into LDS ----
+    auto weight_rows = [&](int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i) {
+            const int rr = 16 * w + i;
+            const char *sbase = (const char *)g.Bt + (size_t)(head * 64 + rr) * g.ldb * 2;
+            const unsigned voff = (unsigned)((l ^ row_swizzle(i)) << 4);
+            if (ROWB == 2048) dma_row_2k(s_lds + A_BYTES + rr * ROWB, voff, sbase);
+            else dma_piece(s_lds + A_BYTES + rr * ROWB, voff, sbase);
+        }
+    };
+    weight_rows(0, 8);
 
     // ---- merged activation rows 4w..4w+3 ----
     // Everything this needs is requested before anything is used: the statistics (one (row, part) pair
@@ -208,11 +225,18 @@ k_vproj_slab(const GemmArgs g)
     // costs one round trip to memory.
     constexpr int HF = ROWB / 1024;
     int slot0[4], np[4];                                 // pieces of the four rows' batch elements (wave-uniform)
+    {
+        // integer divisions are long instruction sequences: the span length is worked out once, and rows of one
+        // batch element (with a beam of four: all four rows of a wavefront) share one look-up
+        const PieceCut cut = piece_cut(g.pm, e_tot);
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) {
-        const int m = min(m0 + 4 * w + ii, g.M - 1);
-        piece_range(g.pm, m / g.x, slot0[ii], np[ii]);
-        np[ii] = min(np[ii], kMaxParts);
+        for (int ii = 0; ii < 4; ++ii) {
+            if (ii > 0 && b_of[ii] == b_of[ii - 1]) { slot0[ii] = slot0[ii - 1]; np[ii] = np[ii - 1]; }
+            else {
+                piece_range(g.pm, cut, b_of[ii], e_lo[ii], e_hi[ii], slot0[ii], np[ii]);
+                np[ii] = min(np[ii], kMaxParts);
+            }
+        }
     }
     auto row_src = [&](int ii, int p, int hf) {
         const int m = min(m0 + 4 * w + ii, g.M - 1);
@@ -243,6 +267,7 @@ k_vproj_slab(const GemmArgs g)
                 xv[ii][hf][pp] = *row_src(ii, pp, hf);
         }
     }
+    weight_rows(8, 16);
     float wgt_lane;
     {
         if (!(lp > 0.f)) { lp = 0.f; mp = -INFINITY; }       // an empty part (its maximum was never written)
