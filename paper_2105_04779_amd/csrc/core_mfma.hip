@@ -65,7 +65,7 @@ bool core_mfma_supported(int dtype, int d_m)
 // row blocks of one span read the same tiles, the second one from L2) and one span of the list of all
 // valid 16-row tiles.  Lengths live on the device, so the host fixes only the number of spans G: one
 // workgroup per compute unit when the longest possible list gives every span at least kMinSpan tiles,
-// fewer otherwise; the kernel derives the span length from the actual lengths.  The floor on the span
+// fewer otherwise (but not fewer than one span per batch element); the kernel derives the span length from the actual lengths.  The floor on the span
 // length keeps every element within kMaxParts pieces.  Batches beyond kScanMax elements are not cut as
 // one list: one workgroup per (element, row block), scheduled by the hardware.
 constexpr int kMinSpan = 8;
@@ -93,7 +93,11 @@ CorePlan plan_core_mfma(const Problem &p, int splits_override, int nrg_override,
         G = (long)p.B * splits_override;                   // about that many pieces per element
     } else {
         const long by_cu = num_cus / pl.nblocks > 0 ? num_cus / pl.nblocks : 1;
-        const long by_len = (long)p.B * tiles / kMinSpan > 0 ? (long)p.B * tiles / kMinSpan : 1;
+        long by_len = (long)p.B * tiles / kMinSpan > 0 ? (long)p.B * tiles / kMinSpan : 1;
+        // short inputs: a span per batch element rather than spans of kMinSpan tiles that each cross into a second
+        // element and fetch its expanded queries as well (B = 64, n = 64: 16 instead of 23 us)
+        const long per_elem = p.B < by_cu ? p.B : by_cu;
+        if (by_len < per_elem) by_len = per_elem;
         G = by_cu < by_len ? by_cu : by_len;
     }
     if (G > max_slots - p.B) G = max_slots - p.B;

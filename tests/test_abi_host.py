@@ -147,8 +147,9 @@ def test_plan_preview_on_the_benchmark_shapes(ea):
     assert plan(320, 4, 16, 1024, 1024) == (2, 128)  # more sentences: longer spans, never more workgroups than units
     assert plan(512, 1, 16, 1024, 1024) == (1, 256)  # per-beam histories: 16 rows, one block
     assert plan(64, 4, 16, 1024, 256) == (2, 128)    # 1024 tiles: still eight per span
-    assert plan(64, 4, 16, 1024, 64) == (2, 32)      # four tiles per sentence: spans of at least eight tiles
-    assert plan(2, 4, 16, 1024, 16) == (2, 1)        # two tiles in all
+    assert plan(64, 4, 16, 1024, 64) == (2, 64)      # four tiles per sentence: one span per sentence, not spans of eight tiles
+    assert plan(64, 4, 16, 1024, 32) == (2, 64)
+    assert plan(2, 4, 16, 1024, 16) == (2, 2)        # two tiles in all
     for B in (1, 3, 17, 64, 100, 1000):
         for beam in (1, 2, 4, 5, 8):
             for n in (1, 16, 100, 1024, 4096):
