@@ -32,9 +32,49 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
            "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    # The resource remarks are read back: the attention core keeps 32 rows of expanded queries or a quarter of the
+    # accumulators in each wavefront's registers, and a change that makes the compiler spill any of them costs a
+    # fifth of the kernel's speed without failing a single test.  A spill there fails the build instead.
+    res = subprocess.run(cmd + ["-Rpass-analysis=kernel-resource-usage"], stderr=subprocess.PIPE, text=True)
+    spilled = check_core_spills(res.stderr)
+    lines = res.stderr.splitlines()
+    if res.returncode != 0:      # everything but the remarks (each is followed by a source line and a caret)
+        skip = 0
+        for ln in lines:
+            if "remark:" in ln:
+                skip = 2
+            elif skip:
+                skip -= 1
+            else:
+                print(ln, file=sys.stderr)
+    elif verbose:
+        for ln in lines:
+            if "warning:" in ln or "error:" in ln:
+                print(ln, file=sys.stderr)
+    sys.stderr.flush()
+    if res.returncode != 0:
+        raise subprocess.CalledProcessError(res.returncode, cmd)
+    if spilled:
+        os.remove(tmp)
+        raise RuntimeError("register spills in the attention core: " + ", ".join(f"{k}: {v}" for k, v in spilled.items()))
     os.replace(tmp, LIB)
     return LIB
+
+
+def check_core_spills(remarks: str) -> dict:
+    """{kernel name: spilled VGPRs} for the instances of k_core_stream that spill, from hipcc's
+    -Rpass-analysis=kernel-resource-usage remarks (a 'Function Name:' line opens each kernel's block)."""
+    import re
+    out, name = {}, None
+    for ln in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", ln)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"VGPRs Spill: (\d+)", ln)
+        if m and name and "k_core_stream" in name and int(m.group(1)) > 0:
+            out[name] = int(m.group(1))
+    return out
 
 
 if __name__ == "__main__":

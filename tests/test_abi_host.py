@@ -178,3 +178,21 @@ def test_check_inputs_rejects_bad_arguments_before_any_device_work(ea):
     assert call(d_model=1020) == I                              # rows not a multiple of 16 bytes
     assert call(H=ctypes.c_void_p(0x10008)) == I                # misaligned H
     assert call(report=ctypes.c_void_p(0x20004)) == I           # misaligned report
+
+
+def test_build_fails_on_register_spills_in_the_attention_core():
+    """The build reads hipcc's resource remarks back: spills in any instance of the core kernel are reported,
+    spills elsewhere and clean instances are not."""
+    from paper_2105_04779_amd import build
+    core = "_ZN2el13k_core_streamILi1024ELb1ELi2ELb0EEEvNS_10StreamArgsE"
+    remarks = "\n".join([
+        f"core_stream.hip:95:1: remark: Function Name: {core} [-Rpass-analysis=kernel-resource-usage]",
+        "core_stream.hip:95:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]",
+        "core_stream.hip:95:1: remark:     VGPRs Spill: 5 [-Rpass-analysis=kernel-resource-usage]",
+        "core_stream.hip:95:1: remark: Function Name: _ZN2el13k_core_streamILi512ELb0ELi1ELb0EEEvNS_10StreamArgsE [-R]",
+        "core_stream.hip:95:1: remark:     VGPRs Spill: 0 [-R]",
+        "gemm_mfma.hip:70:1: remark: Function Name: _ZN2el11k_gemm_slabILb1ELi1EEEvNS_8GemmArgsE [-R]",
+        "gemm_mfma.hip:70:1: remark:     VGPRs Spill: 9 [-R]",
+    ])
+    assert build.check_core_spills(remarks) == {core: 5}
+    assert build.check_core_spills("") == {}
