@@ -2,7 +2,7 @@
 
 Error measure (the whole `out` tensor of a case): max|y - ref| / max|ref|.
 Bars: 1e-5 for fp32 storage, 2e-3 for fp16/bf16 storage with fp32 accumulation.  The worst per-row
-ratio and the relative L2 error are recorded next to the gated figure (gpurun_out/parity_errors.txt).
+ratio and the relative L2 error are recorded next to the gated figure (parity_errors.txt in the run-output folder).
 """
 import numpy as np
 import pytest
