@@ -132,8 +132,8 @@ el_status el_attn_bind_workspace(el_attn_ctx *ctx, void *dev_ptr, size_t bytes);
  *
  * Alignment: where el_attn_uses_mfma(ctx) is 1 the kernels move operands in
  * 16-byte pieces, so H, queries and out must be 16-byte aligned and
- * H_batch_stride * sizeof(element) a multiple of 16 (d_model is 512 or 1024
- * there, so rows are); on the generic path element alignment suffices.
+ * H_batch_stride * sizeof(element) a multiple of 16 (d_model is 512, 768 or
+ * 1024 there, so rows are); on the generic path element alignment suffices.
  * lengths must be 4-byte aligned.  A violation is INVALID_ARG, found on the host
  * before any device work.  el_attn_decode_segment and el_attn_merge_segments
  * apply the same rules to their operands (their fp32 buffers: 4 bytes).
@@ -231,7 +231,7 @@ el_status el_attn_set_row_groups(el_attn_ctx *ctx, int32_t row_groups);
  * What the automatic choice would be for a shape on a device with `compute_units` compute units (host
  * arithmetic only, no device needed): rows per workgroup in groups of 16 (*row_groups) and the number of
  * equal spans the list of valid tiles is cut into (*spans; workgroups = spans x row blocks) by the MFMA
- * attention core.  Errors: INVALID_ARG (null outputs, sizes < 1), UNSUPPORTED (d_model other than 512 or
+ * attention core.  Errors: INVALID_ARG (null outputs, sizes < 1), UNSUPPORTED (d_model other than 512, 768 or
  * 1024: no MFMA core).
  */
 el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d_model, int32_t n,

@@ -367,7 +367,7 @@ el_status el_attn_plan_preview(int32_t B, int32_t beam, int32_t heads, int32_t d
 {
     if (!row_groups || !spans) return EL_ERR_INVALID_ARG;
     if (B < 1 || beam < 1 || heads < 1 || n < 1 || compute_units < 1) return EL_ERR_INVALID_ARG;
-    if (d_model != 512 && d_model != 1024) return EL_ERR_UNSUPPORTED;
+    if (!core_mfma_supported(EL_BF16, d_model)) return EL_ERR_UNSUPPORTED;
     Problem p;
     std::memset(&p, 0, sizeof(p));
     p.B = B; p.beam = beam; p.n = n; p.heads = heads; p.d_m = d_model; p.R = heads * beam;

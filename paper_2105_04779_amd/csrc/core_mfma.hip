@@ -58,7 +58,7 @@ __global__ void k_merge_exp2(const f16_t *__restrict__ Xp, const float *__restri
 // ---------------------------------------------------------------------------------------------
 bool core_mfma_supported(int dtype, int d_m)
 {
-    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024);
+    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 768 || d_m == 1024);
 }
 
 // How the work is cut.  A workgroup takes 16 or 32 of the R = heads x beams rows that share one H (the

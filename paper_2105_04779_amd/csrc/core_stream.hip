@@ -97,8 +97,10 @@ k_core_stream(const StreamArgs a)
     constexpr int ROWB = DM * 2;                    // bytes per tile row (2-byte elements)
     constexpr int SLOT = kTile * ROWB;              // one tile
     constexpr int NSLOT = 4;
-    constexpr int PIECES = ROWB / 1024;             // 1 KB LDS-DMA pieces per row
-    constexpr int NI = 4 * PIECES;                  // fetch instructions per sum wavefront per tile (four rows)
+    constexpr int PIECES = ROWB / 1024;             // 1 KB LDS-DMA pieces per row (rows of 1 or 2 KB)
+    constexpr bool LIN = ROWB % 1024 != 0;          // rows of 1.5 KB: a wavefront's four rows are fetched as one 6 KB block
+    constexpr int NI = 4 * ROWB / 1024;             // fetch instructions per sum wavefront per tile (four rows)
+    constexpr int CPR = ROWB / 16;                  // 16-byte chunks per row
     constexpr int CHK = DM / 128;                   // 32-column chunks of one score wavefront (a quarter of the columns)
     constexpr int DS = DM / 4;                      // columns per sum wavefront
     constexpr int MB = DS / 32;                     // 32-column blocks of the output per sum wavefront
@@ -109,7 +111,8 @@ k_core_stream(const StreamArgs a)
     constexpr int TPL = RG;                         // positions per softmax lane
     constexpr int LPR = 16 / TPL;                   // softmax lanes per row
     constexpr int RPW = 64 / LPR;                   // rows whose softmax one score wavefront does (= ROWS / 4)
-    static_assert(DM == 512 || DM == 1024, "d_m is 512 or 1024");
+    static_assert(DM == 512 || DM == 768 || DM == 1024, "d_m is 512, 768 or 1024");
+    static_assert(LIN ? NI == DM / 128 : true, "one block fetch per 32-column block of a sum wavefront");
     static_assert(RG == 1 || RG == 2, "row groups per workgroup");
 
     __shared__ __attribute__((aligned(1024))) char T[NSLOT * SLOT];
@@ -425,6 +428,9 @@ k_core_stream(const StreamArgs a)
         // (the slot is free when its fetch is requested).  The fetch counter then advances by exactly NI per tile.
         // Everything a request needs is prepared once per tile (f_src, f_dst, f_rows), so that a request is a
         // compare, two selects and the instruction itself.
+        auto dma1k = [&](unsigned dst, unsigned voff, const char *sbase) {
+            if (NT) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase);
+        };
         auto dma = [&](unsigned dst, unsigned voff, const char *sbase) {
             if (PIECES == 2) { if (NT) dma_row_2k_nt(dst, voff, sbase); else dma_row_2k(dst, voff, sbase); }
             else { if (NT) dma_piece_nt(dst, voff, sbase); else dma_piece(dst, voff, sbase); }
@@ -433,11 +439,36 @@ k_core_stream(const StreamArgs a)
         const char *f_src;                                               // row 4v of the tile to request
         unsigned f_dst;                                                  // where that row goes in LDS
         int f_rows;                                                      // rows 4v.. of that tile that exist (<= 0: none)
+        int f_valid = 0;                                                 // block fetch: valid rows of the whole tile (0: no tile)
         auto fetch_setup = [&]() {
             const bool live = f_pos < nspan;
             f_rows = live ? cf.rows() - 4 * v : 0;
-            f_src = (const char *)a.H + ((size_t)min(cf.b, a.B - 1) * a.h_stride * 2 + ((size_t)cf.kt * kTile + 4 * v) * ROWB);
+            f_valid = live ? min(cf.rows(), kTile) : 0;
+            // (block fetch: f_src is row 0 of the tile, the lane offsets carry the row)
+            f_src = (const char *)a.H + ((size_t)min(cf.b, a.B - 1) * a.h_stride * 2 + ((size_t)cf.kt * kTile + (LIN ? 0 : 4 * v)) * ROWB);
             f_dst = t_lds + (f_pos & 3) * SLOT + 4 * v * ROWB;
+        };
+        // Block fetch (rows of 1.5 KB).  The four rows of a wavefront are 6 KB of contiguous memory and of contiguous
+        // LDS: six 1 KB requests, lane l of request j landing at chunk position p = 64 j + l of the block, i.e. row
+        // r = p / CPR, position q = p % CPR, where it must find chunk q ^ swizzle(row) of that row.  A row that does
+        // not exist is replaced by the tile's last valid row (never by memory past the length): its scores are
+        // masked and its probabilities are exactly zero, so a finite stand-in contributes nothing.
+        unsigned lin_off[LIN ? NI : 1];
+        if (LIN) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int pz = 64 * j + l, r = pz / CPR, q = pz - r * CPR;
+                lin_off[j] = (unsigned)((4 * v + r) * ROWB + ((q ^ tile_swizzle(4 * v + r)) << 4));
+            }
+        }
+        auto fetch_lin = [&](int j) {
+            if (f_valid <= 0) dma1k(dz_lds, (unsigned)(l << 4), (const char *)a.H);
+            else if (f_valid >= kTile) dma1k(f_dst + 1024 * j, lin_off[LIN ? j : 0], f_src);
+            else {
+                const int pz = 64 * j + l, r = pz / CPR, q = pz - r * CPR;
+                const int rs = min(4 * v + r, f_valid - 1);
+                dma1k(f_dst + 1024 * j, (unsigned)(rs * ROWB + ((q ^ tile_swizzle(4 * v + r)) << 4)), f_src);
+            }
         };
         // the request of one tile, row by row, so that the weighted sum can spread the four requests over its MFMAs
         // (a request holds its wavefront up while the address unit is busy with the other wavefronts' requests)
@@ -456,8 +487,13 @@ k_core_stream(const StreamArgs a)
             fetch_setup();
         };
         auto fetch_next = [&]() {
+            if (LIN) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) fetch_row(i);
+                for (int j = 0; j < NI; ++j) fetch_lin(j);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) fetch_row(i);
+            }
             fetch_advance();
         };
         // wait until this wavefront's requests of a tile have landed while those of the two tiles after it are
@@ -526,7 +562,8 @@ k_core_stream(const StreamArgs a)
                 if (mb < MB && NP == 2) X[mb] = Mma<BF16>::s32(hfrag, P[NP - 1], X[mb]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (mb > 0) tb[SET][mb - 1][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((EL_LDS(s4) *)(F + b_hi[(mb - 1) & 3] + ((mb - 1) >> 2) * 256));
-                if (mb < MB && mb % (MB / 4) == MB / 4 - 1) fetch_row(mb / (MB / 4));
+                if (LIN) { if (mb < NI) fetch_lin(mb); }
+                else if (mb < MB && mb % (MB / 4 > 0 ? MB / 4 : 1) == (MB / 4 > 0 ? MB / 4 : 1) - 1) fetch_row(mb / (MB / 4 > 0 ? MB / 4 : 1));
             }
             fetch_advance();
             __builtin_amdgcn_sched_barrier(0);
@@ -616,6 +653,7 @@ hipError_t launch_core_stream(const StreamArgs &a, int d_m, bool bf16, int rg, h
 {
     if (a.flat && a.B > kScanMax) return hipErrorInvalidValue;
     if (d_m == 1024) return bf16 ? launch_t<1024, true>(a, rg, s, ev0, ev1) : launch_t<1024, false>(a, rg, s, ev0, ev1);
+    if (d_m == 768) return bf16 ? launch_t<768, true>(a, rg, s, ev0, ev1) : launch_t<768, false>(a, rg, s, ev0, ev1);
     if (d_m == 512) return bf16 ? launch_t<512, true>(a, rg, s, ev0, ev1) : launch_t<512, false>(a, rg, s, ev0, ev1);
     return hipErrorInvalidValue;
 }

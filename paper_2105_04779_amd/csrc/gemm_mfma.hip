@@ -60,7 +60,7 @@ template <> struct Frag<true> {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Slab GEMM: C[M, N] = A[M, K] . Bt[N, K]^T for K = 512 or 1024 (rows of 1 or 2 KB).  One workgroup
+// Slab GEMM: C[M, N] = A[M, K] . Bt[N, K]^T for K = 512, 768 or 1024 (rows of 1, 1.5 or 2 KB).  One workgroup
 // owns a 32 x 32 output tile.  Its 64 operand rows are fetched once, whole, into LDS (row r lands
 // XOR-swizzled by row_swizzle(r % 16), see dma_piece), so global traffic is full cache lines and
 // (M/32 + N/32) passes over the operands in total.  Then wavefront w multiplies k-steps
@@ -80,6 +80,20 @@ k_gemm_slab(const GemmArgs g)
     const unsigned s_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)S;
 
     // ---- stage: wavefronts 0,1 fetch the A rows, 2,3 the Bt rows ----
+    if (rowb == 1536) {
+        // Rows of 1.5 KB do not split into 1 KB pieces: a wavefront's 16 rows are 24 KB of contiguous LDS, filled by
+        // 24 requests; lane l of request j lands at chunk position p = 64 j + l of that block, which is row
+        // r = p / 96, position q = p % 96, and must hold chunk q ^ swizzle(r) of the row.
+        const char *mbase = w < 2 ? (const char *)g.A : (const char *)g.Bt;
+        const int first = w < 2 ? m0 + 16 * w : n0 + 16 * (w - 2);
+        const int lastv = (w < 2 ? g.M : g.N) - 1, ld = w < 2 ? g.lda : g.ldb;
+#pragma unroll
+        for (int j = 0; j < 24; ++j) {
+            const int pz = 64 * j + l, r = pz / 96, q = pz - 96 * r;
+            const unsigned voff = (unsigned)min(first + r, lastv) * (unsigned)(ld * 2) + (unsigned)((q ^ row_swizzle(r)) << 4);
+            dma_piece(s_lds + 16 * w * rowb + 1024 * j, voff, mbase);
+        }
+    } else
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int rr = 16 * w + i;
@@ -208,6 +222,16 @@ k_vproj_slab(const GemmArgs g)
     }
     // ---- weights of this head: rows 16w..16w+15 of its 64, straight into LDS ----
     auto weight_rows = [&](int i0, int i1) {
+        if (ROWB == 1536) {                              // 1.5 KB rows: the rows as one block, see k_gemm_slab
+            const char *sbase = (const char *)g.Bt + (size_t)(head * 64 + 16 * w + i0) * g.ldb * 2;
+#pragma unroll
+            for (int j = 0; j < (i1 - i0) * 3 / 2; ++j) {
+                const int pz = 64 * j + l, r = pz / 96, q = pz - 96 * r;
+                dma_piece(s_lds + A_BYTES + (16 * w + i0) * ROWB + 1024 * j,
+                          (unsigned)(r * g.ldb * 2 + ((q ^ row_swizzle(i0 + r)) << 4)), sbase);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = i0; i < i1; ++i) {
             const int rr = 16 * w + i;
@@ -223,7 +247,8 @@ k_vproj_slab(const GemmArgs g)
     // Everything this needs is requested before anything is used: the statistics (one (row, part) pair
     // per lane), then all partial rows (four rows x the slots in use x both halves), so the whole merge
     // costs one round trip to memory.
-    constexpr int HF = ROWB / 1024;
+    constexpr int HF = (ROWB + 1023) / 1024;             // 64-lane passes over a row of 16-byte chunks (the last may be half used)
+    constexpr int CPR = ROWB / 16;
     int slot0[4], np[4];                                 // pieces of the four rows' batch elements (wave-uniform)
     {
         // integer divisions are long instruction sequences: the span length is worked out once, and rows of one
@@ -264,7 +289,7 @@ k_vproj_slab(const GemmArgs g)
             if (pp >= np[ii]) continue;                  // uniform
 #pragma unroll
             for (int hf = 0; hf < HF; ++hf)
-                xv[ii][hf][pp] = *row_src(ii, pp, hf);
+                if (hf * 64 + l < CPR) xv[ii][hf][pp] = *row_src(ii, pp, hf);
         }
     }
     weight_rows(8, 16);
@@ -305,7 +330,7 @@ k_vproj_slab(const GemmArgs g)
             h8 hv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) hv[e] = (_Float16)v[e];
-            *(h8 *)(S + ar * ROWB + (((hf * 64 + l) ^ row_swizzle(ar)) << 4)) = hv;
+            if (hf * 64 + l < CPR) *(h8 *)(S + ar * ROWB + (((hf * 64 + l) ^ row_swizzle(ar)) << 4)) = hv;
         }
     }
 
@@ -453,7 +478,7 @@ k_elq_slab(const GemmArgs g)
 
 bool gemm_mfma_supported(int dtype, int d_m, int d_k)
 {
-    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 1024) && d_k == 64;
+    return (dtype == EL_F16 || dtype == EL_BF16) && (d_m == 512 || d_m == 768 || d_m == 1024) && d_k == 64;
 }
 
 static GemmArgs base_args(const Problem &p)
@@ -506,6 +531,7 @@ hipError_t launch_vproj_mfma(const el_attn_ctx *ctx, const Problem &p, const Wor
     const int hp = (p.heads + 7) / 8;                    // heads per XCD; 8 * hp * (row tiles) workgroups
     const dim3 grid(8 * hp * ((g.M + 15) / 16)), block(256);
     if (p.d_m == 1024) hipLaunchKernelGGL((k_vproj_slab<1024>), grid, block, 0, s, g);
+    else if (p.d_m == 768) hipLaunchKernelGGL((k_vproj_slab<768>), grid, block, 0, s, g);
     else hipLaunchKernelGGL((k_vproj_slab<512>), grid, block, 0, s, g);
     return hipGetLastError();
 }

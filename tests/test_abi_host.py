@@ -130,9 +130,11 @@ def test_step_operands_are_validated_on_the_host(ea):
     assert call(mfma=0, H=off(H, 2), queries=off(Q, 2), stride=128 * 1024 + 1) == OK
     assert call(mfma=0, H=off(H, 1)) == I and call(mfma=0, out=off(O, 2)) == I and call(mfma=0, lengths=off(L, 1)) == I
     # a shape without MFMA kernels cannot be asked for their rules
+    c640 = _cfg(ea, heads=10, d_model=640, d_k=64, dtype=ea.EL_BF16, max_batch=8, max_beam=4, max_n=128)
+    assert call(cfg=c640, stride=128 * 640) == ea.EL_ERR_UNSUPPORTED
+    assert call(cfg=c640, mfma=0, stride=128 * 640) == OK
     c768 = _cfg(ea, heads=12, d_model=768, d_k=64, dtype=ea.EL_BF16, max_batch=8, max_beam=4, max_n=128)
-    assert call(cfg=c768, stride=128 * 768) == ea.EL_ERR_UNSUPPORTED
-    assert call(cfg=c768, mfma=0, stride=128 * 768) == OK
+    assert call(cfg=c768, stride=128 * 768) == OK                # rows of 1.5 KB have MFMA kernels too
     assert ea.lib.el_attn_check_step_operands(None, 1, H, 1, L, Q, O, 1, 1, 1) == I
 
 
@@ -160,7 +162,8 @@ def test_plan_preview_on_the_benchmark_shapes(ea):
     I = ea.EL_ERR_INVALID_ARG
     assert ea.el_attn_plan_preview(0, 4, 16, 1024, 64, 256)[0] == I
     assert ea.el_attn_plan_preview(4, 4, 16, 1024, 64, 0)[0] == I
-    assert ea.el_attn_plan_preview(4, 4, 16, 768, 64, 256)[0] == ea.EL_ERR_UNSUPPORTED
+    assert ea.el_attn_plan_preview(4, 4, 10, 640, 64, 256)[0] == ea.EL_ERR_UNSUPPORTED
+    assert ea.el_attn_plan_preview(64, 4, 12, 768, 1024, 256)[:2] == (ea.EL_OK, 2)   # 48 rows: two blocks of 32
 
 
 def test_check_inputs_rejects_bad_arguments_before_any_device_work(ea):

@@ -59,7 +59,10 @@ SMALL = [
     ("bf16", 2, 1, 16, 1024, 64, 130, [130, 65]),       # greedy / per-beam history: 16 rows per H
     ("bf16", 2, 6, 16, 1024, 64, 90, [90, 45]),         # beam 6: 96 rows, not a power of two
     ("f16", 2, 3, 8, 512, 64, 77, [77, 5]),             # 24 rows: not a multiple of 16
-    ("bf16", 1, 4, 12, 768, 64, 140, [140]),            # GPT-2-small width
+    ("bf16", 1, 4, 12, 768, 64, 140, [140]),            # GPT-2-small / BART-base width: rows of 1.5 KB
+    ("bf16", 5, 4, 12, 768, 64, 210, [210, 16, 1, 97, 33]),
+    ("f16", 3, 1, 12, 768, 64, 300, [300, 17, 255]),    # per-beam histories at that width: 12 rows per H
+    ("bf16", 40, 2, 12, 768, 64, 50, None),             # 80 query rows: 2.5 row tiles in the projections
     ("f16", 2, 2, 4, 256, 64, 64, [64, 64]),
     ("f16", 2, 2, 4, 512, 128, 90, [90, 41]),           # head size 128: MFMA core between fp32-FMA projections
 ]
@@ -127,7 +130,7 @@ def test_split_count_does_not_change_the_result(splits):
     run_case(w, lens=[300, 70], splits=splits)
 
 
-@pytest.mark.parametrize("dtype,heads,d_m,beam", [("bf16", 16, 1024, 4), ("bf16", 16, 1024, 6), ("f16", 8, 512, 7)])
+@pytest.mark.parametrize("dtype,heads,d_m,beam", [("bf16", 16, 1024, 4), ("bf16", 16, 1024, 6), ("f16", 8, 512, 7), ("bf16", 12, 768, 4)])
 @pytest.mark.parametrize("row_groups,splits", [(1, 1), (1, 3), (2, 1), (2, 2), (2, 5), (1, 8), (2, 8), (0, 0)])
 def test_rows_per_workgroup_and_split_count_do_not_change_the_result(dtype, heads, d_m, beam, row_groups, splits):
     # every cut the automatic plan can choose: 16 or 32 rows per workgroup (one to seven row blocks that
@@ -270,17 +273,24 @@ def test_decode_step_argument_errors():
 # ---- the benchmark configurations at full size ---------------------------------------------------------------
 FULL = ["c2_transformer_base_f16", "c3_bart_large_bf16", "c4_bart_large_b320_bf16",
         "c5_gpt2_medium_n512_bf16", "c5_gpt2_medium_n768_bf16", "c5_gpt2_medium_n1024_bf16"]
-EVERY_ELEMENT = {"c2_transformer_base_f16", "c3_bart_large_bf16"}     # the oracle does these whole batches in seconds
+# the same two decoding set-ups at the width of the base-size models (12 heads, d_m 768: tile rows of 1.5 KB)
+WIDTH_768 = {
+    "w768_beam_search_bf16": wl.custom("w768_beam_search_bf16", dtype="bf16", B=64, beam=4, heads=12, d_m=768, d_k=64,
+                                       n=1024, len_lo=512, len_hi=1024, index=70),
+    "w768_per_beam_history_bf16": wl.custom("w768_per_beam_history_bf16", dtype="bf16", B=512, beam=1, heads=12,
+                                            d_m=768, d_k=64, n=1024, index=71),
+}
+EVERY_ELEMENT = {"c2_transformer_base_f16", "c3_bart_large_bf16", "w768_beam_search_bf16"}   # the oracle does these whole batches in seconds
 
 
-@pytest.mark.parametrize("name", FULL)
+@pytest.mark.parametrize("name", FULL + sorted(WIDTH_768))
 def test_full_size(name):
     """Run the whole batch on the GPU in the launch configuration the benchmark times (same B, n,
     lengths).  The two configurations with 64 sentences are compared in full; of the larger ones the
     oracle computes 16 batch elements (first, last, shortest, longest and twelve spread over the batch),
     element by element; the filler elements are finite noise of the same distribution."""
     import torch
-    w = wl.WORKLOADS[name]
+    w = WIDTH_768[name] if name in WIDTH_768 else wl.WORKLOADS[name]
     W = wl.weights(w)
     L = wl.lengths(w)
     layer = make_layer(w, W)
