@@ -64,6 +64,7 @@ CASES = [
     ("f16", 8, 512, 64, 2, 5, 100, 17, False, 0),
     ("f16", 4, 512, 128, 2, 2, 90, 16, False, 0),         # MFMA core, fp32-FMA projections
     ("bf16", 16, 1024, 64, 2, 2, 80, 12, True, 0),        # generic kernels
+    ("bf16", 12, 768, 64, 3, 4, 130, 21, False, 0),       # base-size width: tile rows of 1.5 KB
 ]
 
 
