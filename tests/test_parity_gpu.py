@@ -93,6 +93,15 @@ def test_many_rows_not_a_multiple_of_the_tile(dtype, B, beam, heads, d_m, n):
 
 
 # ---- degenerate cases ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,B,beam,heads,d_m,n", [("bf16", 1030, 1, 16, 1024, 20), ("bf16", 1100, 2, 12, 768, 18)])
+def test_batches_beyond_the_flattened_cut(dtype, B, beam, heads, d_m, n):
+    """More than 1024 batch elements are not cut as one tile list: one workgroup per (element, row block)."""
+    w = wl.custom(f"wide_batch_{dtype}_{B}_{d_m}", dtype=dtype, B=B, beam=beam, heads=heads, d_m=d_m, d_k=64, n=n, index=55)
+    lens = 1 + (np.arange(B) * 7) % n
+    lens[0], lens[-1] = n, 1
+    run_case(w, lens=lens)
+
+
 def test_single_position_and_single_row():
     w = wl.custom("n1", dtype="bf16", B=2, beam=1, heads=16, d_m=1024, d_k=64, n=1, index=52)
     run_case(w, lens=[1, 1])
